@@ -1,0 +1,286 @@
+/*
+ * CPU oracle for exponential-race speculative-decoding verification.
+ * TEST INFRASTRUCTURE ONLY -- see ersd_oracle.h.  Plain C, fp64, one pass per
+ * row, no blocking or fusion beyond sharing one exponential between the draft
+ * and the target row of a race (which is the method: Section 3 uses the same
+ * realisation of e for P and Q).
+ */
+#include "ersd_oracle.h"
+
+#include <math.h>
+#include <stddef.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+static int g_rounds = 10;
+static int g_threads = 0; /* 0 = OpenMP default */
+
+void oracle_set_rounds(int rounds) { g_rounds = rounds; }
+int oracle_get_rounds(void) { return g_rounds; }
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+    return g_threads > 0 ? g_threads : omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+void oracle_set_num_threads(int n) { g_threads = n; }
+
+/* ---- Philox4x32 (Salmon et al. 2011): two 32x32->64 multiplies per round ---- */
+void oracle_philox4x32(int rounds, const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int r = 0; r < rounds; ++r) {
+        if (r > 0) { /* Weyl key schedule between rounds */
+            k0 += 0x9E3779B9u;
+            k1 += 0xBB67AE85u;
+        }
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* ---- e ~ Exp(1) from a 32-bit word: v uniform on the 2^32 midpoints of (0,1) ---- */
+double oracle_exponential(uint32_t x) {
+    double v = ((double)x + 0.5) * (1.0 / 4294967296.0);
+    return -log1p(-v);
+}
+
+/* Section 3: arrival times map to Gumbel noise through the monotone -log. */
+double oracle_gumbel(uint32_t x) { return -log(oracle_exponential(x)); }
+
+static double widen(const void* row, int dtype, int64_t i) {
+    if (dtype == 0) {
+        return (double)((const float*)row)[i];
+    } else {
+        uint32_t bits = (uint32_t)((const uint16_t*)row)[i] << 16;
+        float f;
+        memcpy(&f, &bits, sizeof f);
+        return (double)f;
+    }
+}
+
+static void finish_info(oracle_row_info* r) {
+    r->exact_tie = 0;
+    r->near_tie = 0;
+    if (r->runner_up < 0) return;
+    if (r->s1 == r->s2) { /* also covers -inf == -inf */
+        r->exact_tie = 1;
+        r->near_tie = 1;
+        return;
+    }
+    double scale = fabs(r->s1) > 1.0 ? fabs(r->s1) : 1.0;
+    if (r->s1 - r->s2 <= 1e-6 * scale) r->near_tie = 1;
+}
+
+void oracle_race_rows(const void* const rows[2], int dtype, int64_t V, float temperature,
+                      uint64_t seed, uint32_t c1, uint32_t c2, uint32_t c3,
+                      oracle_row_info info[2]) {
+    const uint32_t key[2] = {(uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32)};
+    const double T = (double)temperature;
+    for (int s = 0; s < 2; ++s) {
+        info[s].token = -1;
+        info[s].runner_up = -1;
+        info[s].s1 = -INFINITY;
+        info[s].s2 = -INFINITY;
+        info[s].near_tie = 0;
+        info[s].exact_tie = 0;
+    }
+    uint32_t words[4] = {0, 0, 0, 0};
+    for (int64_t i = 0; i < V; ++i) {
+        if ((i & 3) == 0) {
+            const uint32_t ctr[4] = {(uint32_t)(i >> 2), c1, c2, c3};
+            oracle_philox4x32(g_rounds, ctr, key, words);
+        }
+        const double g = oracle_gumbel(words[i & 3]); /* -ln e_i, shared by both sides */
+        for (int s = 0; s < 2; ++s) {
+            if (!rows[s]) continue;
+            /* argmin e_i / p_i  ==  argmax  l_i/T - ln e_i  (normaliser dropped) */
+            const double score = widen(rows[s], dtype, i) / T + g;
+            oracle_row_info* r = &info[s];
+            if (r->token < 0) { /* first token */
+                r->token = (int32_t)i;
+                r->s1 = score;
+            } else if (score > r->s1) { /* strictly better: new winner, old winner becomes runner-up */
+                r->runner_up = r->token;
+                r->s2 = r->s1;
+                r->token = (int32_t)i;
+                r->s1 = score;
+            } else if (r->runner_up < 0 || score > r->s2) { /* ties keep the lower index */
+                r->runner_up = (int32_t)i;
+                r->s2 = score;
+            }
+        }
+    }
+    for (int s = 0; s < 2; ++s)
+        if (rows[s]) finish_info(&info[s]);
+}
+
+int64_t oracle_row_candidates(const void* row, int dtype, int64_t V, float temperature,
+                              uint64_t seed, uint32_t c1, uint32_t c2, uint32_t c3,
+                              double tol_rel, int32_t* out_idx, int64_t cap) {
+    const void* rows[2] = {row, NULL};
+    oracle_row_info info[2];
+    oracle_race_rows(rows, dtype, V, temperature, seed, c1, c2, c3, info);
+    const double s1 = info[0].s1;
+    const double scale = fabs(s1) > 1.0 ? fabs(s1) : 1.0;
+    const uint32_t key[2] = {(uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32)};
+    const double T = (double)temperature;
+    uint32_t words[4] = {0, 0, 0, 0};
+    int64_t n = 0;
+    for (int64_t i = 0; i < V; ++i) {
+        if ((i & 3) == 0) {
+            const uint32_t ctr[4] = {(uint32_t)(i >> 2), c1, c2, c3};
+            oracle_philox4x32(g_rounds, ctr, key, words);
+        }
+        const double score = widen(row, dtype, i) / T + oracle_gumbel(words[i & 3]);
+        if (score == s1 || s1 - score <= tol_rel * scale) {
+            if (n < cap) out_idx[n] = (int32_t)i;
+            ++n;
+        }
+    }
+    return n;
+}
+
+static size_t elem_size(int dtype) { return dtype == 0 ? 4 : 2; }
+
+static int bad_common(const void* draft, const void* target, int dtype, int64_t V, float T) {
+    if (!draft || !target) return 1;
+    if (dtype != 0 && dtype != 1) return 1;
+    if (V < 1 || V > 2147483647LL) return 1;
+    if (!(T > 0.0f) || !isfinite(T)) return 1;
+    return 0;
+}
+
+/* Leading positions where the draft and target winners agree (Section 2:
+ * drafted tokens are accepted in order until the first rejection). */
+static int32_t accepted_prefix(const int32_t* d, const int32_t* t, int32_t k) {
+    int32_t a = 0;
+    while (a < k && d[a] == t[a]) ++a;
+    return a;
+}
+
+int oracle_race_verify_multi(const void* draft, const void* target, int dtype,
+                             int32_t B, int32_t m, int32_t k, int64_t V,
+                             float temperature, uint64_t seed,
+                             int32_t* draft_tokens, int32_t* target_tokens, int32_t* accept_len,
+                             int32_t* best_draft, int32_t* best_len,
+                             oracle_row_info* draft_info, oracle_row_info* target_info) {
+    if (bad_common(draft, target, dtype, V, temperature)) return -1;
+    if (B < 1 || m < 1 || k < 1 || !draft_tokens || !target_tokens || !accept_len) return -1;
+    const size_t es = elem_size(dtype);
+    const int64_t nrace = (int64_t)B * m * (k + 1);
+    if (g_threads > 0) {
+#ifdef _OPENMP
+        omp_set_num_threads(g_threads);
+#endif
+    }
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t r = 0; r < nrace; ++r) {
+        const int32_t j = (int32_t)(r % (k + 1));
+        const int32_t d = (int32_t)((r / (k + 1)) % m);
+        const int32_t b = (int32_t)(r / ((int64_t)(k + 1) * m));
+        const int64_t seq = (int64_t)b * m + d;
+        /* position k is the bonus position: a target-only race (Algorithm 2's
+         * extra token after an accepted draft, drawn here by a fresh race). */
+        const char* drow = j < k ? (const char*)draft + (size_t)((seq * k + j) * V) * es : NULL;
+        const char* trow = (const char*)target + (size_t)((seq * (k + 1) + j) * V) * es;
+        const void* rows[2] = {drow, trow};
+        oracle_row_info info[2];
+        oracle_race_rows(rows, dtype, V, temperature, seed, (uint32_t)j, (uint32_t)b, (uint32_t)d, info);
+        if (j < k) {
+            draft_tokens[seq * k + j] = info[0].token;
+            if (draft_info) draft_info[seq * k + j] = info[0];
+        }
+        target_tokens[seq * (k + 1) + j] = info[1].token;
+        if (target_info) target_info[seq * (k + 1) + j] = info[1];
+    }
+    for (int64_t seq = 0; seq < (int64_t)B * m; ++seq)
+        accept_len[seq] = accepted_prefix(draft_tokens + seq * k, target_tokens + seq * (k + 1), k);
+    if (best_draft && best_len) {
+        for (int32_t b = 0; b < B; ++b) {
+            int32_t bl = -1, bd = -1;
+            for (int32_t d = 0; d < m; ++d) {
+                if (accept_len[(int64_t)b * m + d] > bl) {
+                    bl = accept_len[(int64_t)b * m + d];
+                    bd = d;
+                }
+            }
+            best_len[b] = bl;
+            best_draft[b] = bd;
+        }
+    }
+    return 0;
+}
+
+int oracle_race_verify(const void* draft, const void* target, int dtype,
+                       int32_t B, int32_t k, int64_t V, float temperature, uint64_t seed,
+                       int32_t* draft_tokens, int32_t* target_tokens, int32_t* accept_len,
+                       oracle_row_info* draft_info, oracle_row_info* target_info) {
+    /* the sequence variant is the multi-draft layout with one draft (counter word 3 = 0) */
+    return oracle_race_verify_multi(draft, target, dtype, B, 1, k, V, temperature, seed,
+                                    draft_tokens, target_tokens, accept_len, NULL, NULL,
+                                    draft_info, target_info);
+}
+
+int oracle_race_verify_tree(const void* draft, const void* target, int dtype,
+                            int32_t B, int32_t N, int64_t V, const int32_t* parent,
+                            float temperature, uint64_t seed,
+                            int32_t* draft_tokens, int32_t* target_tokens,
+                            int32_t* accept_len, int32_t* accept_node,
+                            oracle_row_info* draft_info, oracle_row_info* target_info) {
+    if (bad_common(draft, target, dtype, V, temperature)) return -1;
+    if (B < 1 || N < 1 || !parent || !draft_tokens || !target_tokens || !accept_len) return -1;
+    const size_t es = elem_size(dtype);
+    const int64_t nrace = (int64_t)B * N;
+    if (g_threads > 0) {
+#ifdef _OPENMP
+        omp_set_num_threads(g_threads);
+#endif
+    }
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t r = 0; r < nrace; ++r) {
+        const int32_t n = (int32_t)(r % N);
+        const int32_t b = (int32_t)(r / N);
+        const void* rows[2] = {(const char*)draft + (size_t)(r * V) * es,
+                               (const char*)target + (size_t)(r * V) * es};
+        oracle_row_info info[2];
+        oracle_race_rows(rows, dtype, V, temperature, seed, (uint32_t)n, (uint32_t)b, 0u, info);
+        draft_tokens[r] = info[0].token;
+        target_tokens[r] = info[1].token;
+        if (draft_info) draft_info[r] = info[0];
+        if (target_info) target_info[r] = info[1];
+    }
+    /* A node is accepted iff the two winners agree at it and at every ancestor
+     * (Section 4: a vertex can only be accepted if its ancestors are). */
+    for (int32_t b = 0; b < B; ++b) {
+        int32_t best_depth = 0, best_node = -1;
+        for (int32_t n = 0; n < N; ++n) {
+            int32_t depth = 0, ok = 1, cur = n, steps = 0;
+            while (1) {
+                if (draft_tokens[(int64_t)b * N + cur] != target_tokens[(int64_t)b * N + cur]) { ok = 0; break; }
+                ++depth;
+                const int32_t p = parent[cur];
+                if (p == -1) break;
+                if (p < 0 || p >= cur || ++steps > N) { ok = 0; break; } /* malformed tree */
+                cur = p;
+            }
+            if (ok && depth > best_depth) {
+                best_depth = depth;
+                best_node = n;
+            }
+        }
+        accept_len[b] = best_depth;
+        if (accept_node) accept_node[b] = best_node;
+    }
+    return 0;
+}

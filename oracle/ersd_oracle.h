@@ -1,0 +1,119 @@
+/*
+ * CPU oracle for exponential-race speculative-decoding verification (ERSD).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This is the slow, plain, fp64 definition of what
+ * the GPU library must compute.  It shares no code with the HIP path and is
+ * never linked into it; only the tests, the smoke check and the CPU-baseline
+ * leg of the benchmark may call it.
+ *
+ * All pointers are HOST pointers owned by the caller.  Logit tensors are
+ * row-major with the vocabulary innermost; dtype 0 = IEEE fp32, dtype 1 =
+ * bfloat16 (upper 16 bits of an fp32, widened exactly).
+ *
+ * What is computed (paper: Section 3 "Exponential Races", Algorithm 2 for
+ * k = 1, the sequence extension of Section 3, Algorithm 5 for trees):
+ *   one race per context: e_i ~ Exp(1) for every token i, the draft token is
+ *   argmin_i e_i / Q(i), the target token is argmin_i e_i / P(i) with the SAME
+ *   e; a drafted token is accepted while the two winners agree.
+ * With P = softmax(l_p / T), Q = softmax(l_q / T) and the monotone map -log
+ * (Section 3 calls this the Gumbel-max form) argmin e_i/p_i equals
+ * argmax_i ( l_i / T - ln e_i ), because the softmax normaliser does not
+ * depend on i.
+ *
+ * Readings the paper leaves open (RNG, bit layout, tie-break, temperature):
+ *   e_i = -log1p(-v),  v = (x + 1/2) * 2^-32,  x = word (i & 3) of
+ *   Philox4x32-R( counter = (i >> 2, position-or-node, sequence, draft),
+ *                 key = (seed low word, seed high word) ),  R = 10 by default;
+ *   exact score ties go to the lowest token index.
+ */
+#ifndef ERSD_ORACLE_H
+#define ERSD_ORACLE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Philox4x32 with `rounds` rounds (Salmon, Moraes, Dror, Shaw 2011). */
+void oracle_philox4x32(int rounds, const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
+
+/* Number of Philox rounds used by every race below (default 10). */
+void oracle_set_rounds(int rounds);
+int oracle_get_rounds(void);
+
+/* Exp(1) variate and its Gumbel -ln(e) from one 32-bit word. */
+double oracle_exponential(uint32_t x);
+double oracle_gumbel(uint32_t x);
+
+/* Per-row diagnostics, one entry per logit row that was raced. */
+typedef struct {
+    int32_t token;      /* lowest index attaining the maximum score            */
+    int32_t runner_up;  /* index of the best score among the other tokens, -1 if V == 1 */
+    double s1;          /* winning score  l/T - ln e  (natural-log units)      */
+    double s2;          /* runner-up score (-inf if V == 1)                    */
+    int32_t near_tie;   /* 1 iff s1 - s2 <= 1e-6 * max(1, |s1|) (or s1 == s2)  */
+    int32_t exact_tie;  /* 1 iff s1 == s2                                      */
+} oracle_row_info;
+
+/*
+ * One race over up to two rows that share the same exponentials.
+ * rows[s] may be NULL for an absent side.  c1, c2, c3 are counter words 1..3.
+ */
+void oracle_race_rows(const void* const rows[2], int dtype, int64_t V, float temperature,
+                      uint64_t seed, uint32_t c1, uint32_t c2, uint32_t c3,
+                      oracle_row_info info[2]);
+
+/* Tokens whose score is within tol_rel * max(1,|s1|) of the row maximum, in
+ * increasing index order; returns how many exist (writes at most cap). */
+int64_t oracle_row_candidates(const void* row, int dtype, int64_t V, float temperature,
+                              uint64_t seed, uint32_t c1, uint32_t c2, uint32_t c3,
+                              double tol_rel, int32_t* out_idx, int64_t cap);
+
+/*
+ * Sequence variant.  draft [B,k,V], target [B,k+1,V].
+ * draft_tokens [B,k], target_tokens [B,k+1], accept_len [B];
+ * draft_info [B,k] and target_info [B,k+1] may be NULL.
+ * Returns 0, or -1 on invalid arguments.
+ */
+int oracle_race_verify(const void* draft, const void* target, int dtype,
+                       int32_t B, int32_t k, int64_t V, float temperature, uint64_t seed,
+                       int32_t* draft_tokens, int32_t* target_tokens, int32_t* accept_len,
+                       oracle_row_info* draft_info, oracle_row_info* target_info);
+
+/*
+ * Multi-draft variant (workload definition, not a procedure of the paper):
+ * draft [B,m,k,V], target [B,m,k+1,V]; counter word 3 is the draft index.
+ * accept_len [B,m]; best_len[b] = max over drafts, best_draft[b] = lowest
+ * draft index attaining it.
+ */
+int oracle_race_verify_multi(const void* draft, const void* target, int dtype,
+                             int32_t B, int32_t m, int32_t k, int64_t V,
+                             float temperature, uint64_t seed,
+                             int32_t* draft_tokens, int32_t* target_tokens, int32_t* accept_len,
+                             int32_t* best_draft, int32_t* best_len,
+                             oracle_row_info* draft_info, oracle_row_info* target_info);
+
+/*
+ * Tree variant: one race per node (counter word 1 = node index), draft and
+ * target [B,N,V], parent[N] shared by all sequences with parent[n] == -1 for
+ * children of the (token-less) root and 0 <= parent[n] < n otherwise; any
+ * other value makes node n (and its descendants) unaccepted.
+ * accept_len[b] = depth of the deepest node whose whole root path agrees
+ * (0 if none), accept_node[b] = lowest such node index (-1 if none).
+ */
+int oracle_race_verify_tree(const void* draft, const void* target, int dtype,
+                            int32_t B, int32_t N, int64_t V, const int32_t* parent,
+                            float temperature, uint64_t seed,
+                            int32_t* draft_tokens, int32_t* target_tokens,
+                            int32_t* accept_len, int32_t* accept_node,
+                            oracle_row_info* draft_info, oracle_row_info* target_info);
+
+/* Threads the row loops will use (OpenMP), for reporting. */
+int oracle_num_threads(void);
+void oracle_set_num_threads(int n);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,192 @@
+"""Pins for the CPU oracle: what the paper and the mathematics fix, checked without a GPU."""
+import math
+import os
+
+import numpy as np
+import pytest
+from scipy import stats
+
+import mini_oracle
+import theory
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ----------------------------------------------------------------------------- generator
+def test_philox_known_answers(oracle_mod):
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "philox4x32_10_kat.txt")) if l.strip() and l[0] != "#"]
+    assert len(rows) == 3
+    for r in rows:
+        v = [int(x, 16) for x in r]
+        out = oracle_mod.philox4x32(v[0:4], v[4:6], 10)
+        assert [int(x) for x in out] == v[6:10]
+        assert mini_oracle.philox4x32(v[0:4], v[4:6], 10) == v[6:10]
+
+
+def test_philox_round_count_matters(oracle_mod):
+    a = oracle_mod.philox4x32([1, 2, 3, 4], [5, 6], 10)
+    b = oracle_mod.philox4x32([1, 2, 3, 4], [5, 6], 7)
+    assert list(a) != list(b)
+    assert oracle_mod.get_rounds() == 10
+
+
+def test_philox_matches_independent_python_version(oracle_mod):
+    rng = np.random.default_rng(7)
+    for _ in range(200):
+        ctr = rng.integers(0, 2**32, size=4, dtype=np.uint64)
+        key = rng.integers(0, 2**32, size=2, dtype=np.uint64)
+        assert [int(x) for x in oracle_mod.philox4x32(ctr, key, 10)] == mini_oracle.philox4x32(ctr, key, 10)
+
+
+# ----------------------------------------------------------------------------- Exp(1) transform
+def test_exponential_closed_form_values(oracle_mod):
+    ln2 = math.log(2.0)
+    # x = 0: v = 2^-33, -log1p(-v) = v + v^2/2 + ...
+    v = 2.0**-33
+    assert oracle_mod.exponential(0) == pytest.approx(v + v * v / 2, rel=1e-15)
+    assert oracle_mod.gumbel(0) == pytest.approx(33 * ln2 - v / 2, rel=1e-14)   # -ln(v (1 + v/2))
+    # x = 2^31: 1 - v = 1/2 - 2^-33  =>  e = ln 2 - ln(1 - 2^-32)
+    assert oracle_mod.exponential(2**31) == pytest.approx(ln2 - math.log1p(-(2.0**-32)), rel=1e-15)
+    assert oracle_mod.gumbel(2**31) == pytest.approx(-math.log(ln2), abs=1e-9)  # 0.36651292...
+    # x = 2^32 - 1: 1 - v = 2^-33  =>  e = 33 ln 2
+    assert oracle_mod.exponential(2**32 - 1) == pytest.approx(33 * ln2, rel=1e-15)
+    assert oracle_mod.gumbel(2**32 - 1) == pytest.approx(-math.log(33 * ln2), rel=1e-14)
+
+
+def test_exponential_is_increasing_and_positive(oracle_mod):
+    xs = [0, 1, 2, 1000, 2**20, 2**31 - 1, 2**31, 2**32 - 2, 2**32 - 1]
+    es = [oracle_mod.exponential(x) for x in xs]
+    assert all(e > 0 and math.isfinite(e) for e in es)
+    assert all(a < b for a, b in zip(es, es[1:]))
+
+
+def test_exponential_law_of_generated_stream(oracle_mod):
+    """The exponentials a race uses (consecutive counters of one context) follow Exp(1)."""
+    n_calls = 50000
+    words = np.concatenate([oracle_mod.philox4x32([i, 3, 5, 0], [11, 0], 10) for i in range(n_calls)])
+    e = np.array([oracle_mod.exponential(int(x)) for x in words[:100000]])
+    n = len(e)
+    assert abs(e.mean() - 1.0) < 5 / math.sqrt(n)            # sd of Exp(1) is 1
+    assert abs(e.var() - 1.0) < 5 * math.sqrt(8.0 / n)        # var of (e-1)^2 is 8
+    assert stats.kstest(e, "expon").pvalue > 1e-3
+
+
+# ----------------------------------------------------------------------------- winner law (Section 3)
+@pytest.mark.parametrize("V,T", [(4, 1.0), (8, 0.7), (16, 1.3)])
+def test_race_winner_follows_softmax(oracle_mod, V, T):
+    """Section 3: the race winner argmin e_i / p_i is distributed as P.  Chi-square on >= 1e5 races."""
+    rng = np.random.default_rng(100 + V)
+    lq = rng.normal(0, 1.5, size=V).astype(np.float32)
+    lp = (lq + rng.normal(0, 0.7, size=V)).astype(np.float32)
+    k = 120000
+    draft = np.broadcast_to(lq, (1, k, V)).copy()
+    target = np.broadcast_to(lp, (1, k + 1, V)).copy()
+    out = oracle_mod.race_verify(draft, target, T, seed=12345)
+    n = k
+    for toks, logits in ((out["draft_tokens"][0], lq), (out["target_tokens"][0, :k], lp)):
+        expected = theory.softmax(logits.astype(np.float64), float(np.float32(T))) * n
+        counts = np.bincount(toks, minlength=V)
+        chi2 = ((counts - expected) ** 2 / expected).sum()
+        assert stats.chi2.sf(chi2, V - 1) > 1e-4, (chi2, counts, expected)
+
+
+def test_log_form_equals_literal_argmin_form(oracle_mod):
+    """Section 3 (Gumbel-max remark): argmax(l/T - ln e) picks the same token as argmin e / softmax(l/T)."""
+    rng = np.random.default_rng(5)
+    for trial in range(40):
+        V = int(rng.integers(1, 65))
+        k = 3
+        T = float(rng.choice([0.5, 0.7, 1.0, 2.0]))
+        target = rng.normal(0, 3, size=(2, k + 1, V)).astype(np.float32)
+        draft = (target[:, :k] + rng.normal(0, 0.8, size=(2, k, V))).astype(np.float32)
+        seed = int(rng.integers(0, 2**63))
+        o = oracle_mod.race_verify(draft, target, T, seed)
+        dt, tt, acc = mini_oracle.race_verify(draft.astype(np.float64), target.astype(np.float64), T, seed)
+        assert np.array_equal(o["draft_tokens"], dt)
+        assert np.array_equal(o["target_tokens"], tt)
+        assert np.array_equal(o["accept_len"], acc)
+
+
+def test_bf16_rows_are_widened_exactly(oracle_mod):
+    rng = np.random.default_rng(6)
+    V, k = 48, 2
+    bits_t = (rng.normal(0, 3, size=(1, k + 1, V)).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    bits_d = (rng.normal(0, 3, size=(1, k, V)).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    o = oracle_mod.race_verify(bits_d, bits_t, 1.0, 99)
+    dt, tt, acc = mini_oracle.race_verify(mini_oracle.bf16_to_f64(bits_d), mini_oracle.bf16_to_f64(bits_t), 1.0, 99)
+    assert np.array_equal(o["draft_tokens"], dt) and np.array_equal(o["target_tokens"], tt)
+    assert np.array_equal(o["accept_len"], acc)
+    # and the same values given as fp32 must give the same answer
+    o32 = oracle_mod.race_verify(mini_oracle.bf16_to_f64(bits_d).astype(np.float32),
+                                 mini_oracle.bf16_to_f64(bits_t).astype(np.float32), 1.0, 99)
+    assert np.array_equal(o32["target_tokens"], o["target_tokens"])
+
+
+# ----------------------------------------------------------------------------- coupling (Lemma 3.1)
+def test_coupling_closed_form_against_brute_force():
+    rng = np.random.default_rng(3)
+    for V in (2, 3, 5, 8):
+        p = theory.softmax(rng.normal(0, 1.5, V))
+        q = theory.softmax(rng.normal(0, 1.5, V))
+        c = theory.coupling_probability(p, q)
+        assert c == pytest.approx(theory.coupling_probability_sorted(p, q), rel=1e-12)
+        mc = theory.coupling_monte_carlo(p, q, 1_000_000, seed=V)
+        assert abs(mc - c) < 5 * math.sqrt(c * (1 - c) / 1_000_000)
+        # Lemma 3.1 sandwich
+        assert theory.harmonic_mean_distance(p, q) - 1e-12 <= c <= 1 - theory.total_variation(p, q) + 1e-12
+
+
+def test_coupling_two_token_case_reaches_total_variation_bound():
+    p, q = np.array([0.5, 0.5]), np.array([0.75, 0.25])
+    assert theory.coupling_probability(p, q) == pytest.approx(0.75, rel=1e-14)       # 1 - D_TV
+    assert theory.harmonic_mean_distance(p, q) == pytest.approx(0.3 + 1 / 6, rel=1e-14)
+
+
+@pytest.mark.parametrize("V", [3, 8])
+def test_oracle_match_rate_equals_coupling_probability(oracle_mod, V):
+    """Empirical draft/target agreement of the oracle vs the closed form and the Lemma 3.1 bounds; plus the
+    Poisson-matching-lemma bound on the mismatch rate conditional on the draft winner (Appendix B)."""
+    rng = np.random.default_rng(40 + V)
+    lq = rng.normal(0, 1.2, size=V).astype(np.float32)
+    lp = (lq + rng.normal(0, 0.8, size=V)).astype(np.float32)
+    k = 200000
+    out = oracle_mod.race_verify(np.broadcast_to(lq, (1, k, V)).copy(), np.broadcast_to(lp, (1, k + 1, V)).copy(),
+                                 1.0, seed=777)
+    d, t = out["draft_tokens"][0], out["target_tokens"][0, :k]
+    p, q = theory.softmax(lp.astype(np.float64)), theory.softmax(lq.astype(np.float64))
+    c = theory.coupling_probability(p, q)
+    rate = float((d == t).mean())
+    assert abs(rate - c) < 4.5 * math.sqrt(c * (1 - c) / k)
+    assert theory.harmonic_mean_distance(p, q) <= rate + 0.005
+    assert rate <= 1 - theory.total_variation(p, q) + 0.005
+    for i in range(V):
+        sel = d == i
+        if sel.sum() < 2000:
+            continue
+        mism = float((t[sel] != i).mean())
+        bound = 1 - 1 / (1 + q[i] / p[i])
+        assert mism <= bound + 4.5 * math.sqrt(0.25 / sel.sum())
+    # accepted prefix = run of leading agreements
+    assert out["accept_len"][0] == int(np.argmin(np.concatenate((d == t, [False]))))
+
+
+def test_mean_accept_length_matches_closed_form_expectation(oracle_mod):
+    """E[accept_len] = sum_j prod_{l<=j} alpha_l with alpha from the closed form on the actual rows."""
+    rng = np.random.default_rng(11)
+    B, k, V = 1500, 4, 24
+    target = rng.normal(0, 2.0, size=(B, k + 1, V)).astype(np.float32)
+    draft = (target[:, :k] + rng.normal(0, 0.6, size=(B, k, V))).astype(np.float32)
+    out = oracle_mod.race_verify(draft, target, 0.9, seed=2024)
+    T = float(np.float32(0.9))
+    mean, var = 0.0, 0.0
+    for b in range(B):
+        alpha = [theory.coupling_probability_sorted(theory.softmax(target[b, j].astype(np.float64), T),
+                                                    theory.softmax(draft[b, j].astype(np.float64), T))
+                 for j in range(k)]
+        surv = np.cumprod(alpha)                      # P(accept_len >= j+1)
+        m1 = surv.sum()
+        m2 = sum((2 * (j + 1) - 1) * surv[j] for j in range(k))   # E[L^2] = sum (2j-1) P(L >= j)
+        mean += m1
+        var += m2 - m1 * m1
+    z = (out["accept_len"].sum() - mean) / math.sqrt(var)
+    assert abs(z) < 4.5, z
