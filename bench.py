@@ -1,0 +1,162 @@
+#!/usr/bin/env python3
+"""Throughput of the exponential-race verification hot path on one MI355X.
+
+One "step" is one pass of the whole hot path (race kernel + acceptance kernel) over one batch of synthetic
+logits that are already resident in HBM.  The default workload is the B=64, k=8, V=128256 bf16 sequence
+configuration the headline metric is quoted on.  Prints ONE JSON line.
+
+The step is issued as its two stages (ersd_race_stage_races, ersd_race_stage_accept -- together exactly
+ersd_race_verify*) so that a HIP event can be recorded between them: the race kernel's own duration is
+measured inside the timed region and priced against the HBM roofline.  Input buffers rotate over several
+distinct sets so that the 256 MB on-die cache cannot serve the reads.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import torch
+
+PEAK_HBM_GBS = 8000.0
+
+# HBM bytes per race-kernel launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a copy
+# kernel of known size; filled in from the summaries under profiles/ (None = not measured for that workload).
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=1, help="index into the five benchmark workloads (default 1)")
+    ap.add_argument("--buffers", type=int, default=4, help="distinct input sets rotated through (cache defeat)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--fused-call", action="store_true",
+                    help="issue each step through the single verify entry point (no event between the stages)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus must be 1",
+              file=sys.stderr)
+        return 2
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
+        return 2
+
+    from paper_2504_15475_amd import race, workloads as wl
+    race.lib()
+    w = wl.WORKLOADS[args.workload]
+    variant = {"sequence": race.VARIANT_SEQUENCE, "multi": race.VARIANT_MULTI, "tree": race.VARIANT_TREE}[w.variant]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    base = wl.make_inputs(w, dev)
+    sets = [base]
+    for i in range(1, max(1, args.buffers)):
+        # further sets: same distribution, different values (a cheap permutation of rows would alias in cache)
+        g = torch.Generator(device=dev).manual_seed(5000 + i)
+        noise = lambda x: (x.float() + 0.01 * torch.randn(x.shape, generator=g, device=dev)).to(x.dtype).contiguous()
+        s = dict(draft=noise(base["draft"]), target=noise(base["target"]))
+        if "parent" in base:
+            s["parent"] = base["parent"]
+        sets.append(s)
+    calls = [race.PreparedVerify(variant, s["draft"], s["target"], w.temperature, w.seed, s.get("parent")) for s in sets]
+    torch.cuda.synchronize()
+
+    def step(i, mid=None):
+        c = calls[i % len(calls)]
+        if args.fused_call:
+            c.run()
+        else:
+            c.run_stages(mid)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    K = args.steps
+    ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(K)]
+    ev1 = [torch.cuda.Event(enable_timing=True) for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        if not args.fused_call:
+            ev0[i].record()
+        step(i, None if args.fused_call else ev1[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    total_s = t1 - t0
+    ms_per_step = total_s * 1e3 / K
+    value = w.race_elements * K / total_s
+    if args.fused_call:
+        kernel_ms = None
+    else:
+        durs = sorted(a.elapsed_time(b) for a, b in zip(ev0, ev1))
+        kernel_ms = sum(durs) / len(durs)
+    algo_bytes = w.logit_bytes
+    roofline = None
+    if kernel_ms:
+        achieved = algo_bytes / (kernel_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(w.index),
+                    "kernel": "race_filtered_kernel", "kernel_ms_avg": round(kernel_ms, 5),
+                    "kernel_ms_min": round(durs[0], 5), "kernel_ms_median": round(durs[len(durs) // 2], 5),
+                    "algorithmic_bytes_per_launch": algo_bytes}
+
+    out = {
+        "metric": "race_elements_per_sec", "value": value, "unit": "elements/s", "n_gpus": 1, "steps": K,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f64",
+        "data": "synthetic",
+        "config": {"workload": w.name, "description": wl.describe(w), "race_elements_per_step": w.race_elements,
+                   "logit_dtype": "bf16" if w.elem_bytes == 2 else "fp32", "input_buffer_sets": len(calls),
+                   "arithmetic": "u32 Philox + f32 bound filter on every token, f64 scores on surviving candidates",
+                   "issue": "verify entry point" if args.fused_call else "two stage entry points + event"},
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"], out["check"] = cpu_baseline(w, base, calls[0], variant)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+def cpu_baseline(w, base, call, variant):
+    """The CPU oracle, as it stands, on a bounded sample of the same inputs, timed on this machine's host cores; its
+    tokens are also compared with the GPU's on that sample."""
+    import numpy as np
+    import oracle
+    from paper_2504_15475_amd import race
+    # sample: leading sequences, sized to roughly 10-30 s of CPU work at ~60 ns per token position
+    per_seq_positions = (w.m * (w.k + 1) if w.variant != "tree" else w.N) * w.V
+    nseq = max(1, min(w.B, int(3.0e8 // per_seq_positions)))
+    d = base["draft"][:nseq].contiguous().cpu()
+    t = base["target"][:nseq].contiguous().cpu()
+    oracle.race_rows(None, t.reshape(-1, w.V)[0], w.temperature, w.seed)  # warm-up (library load, page-in)
+    t0 = time.perf_counter()
+    if variant == race.VARIANT_SEQUENCE:
+        o = oracle.race_verify(d, t, w.temperature, w.seed, want_info=True)
+    elif variant == race.VARIANT_MULTI:
+        o = oracle.race_verify_multi(d, t, w.temperature, w.seed, want_info=True)
+    else:
+        o = oracle.race_verify_tree(d, t, base["parent"].cpu().numpy(), w.temperature, w.seed, want_info=True)
+    dt = time.perf_counter() - t0
+    elements = w.race_elements * nseq // w.B
+    call.run()
+    torch.cuda.synchronize()
+    gpu = [x.cpu().numpy() for x in call.outputs()]
+    mism = int((gpu[0][:nseq] != o["draft_tokens"]).sum() + (gpu[1][:nseq] != o["target_tokens"]).sum())
+    mism_acc = int((gpu[2][:nseq] != o["accept_len"]).sum())
+    near = int(o["draft_info"]["near_tie"].sum() + o["target_info"]["near_tie"].sum())
+    base_out = {"value": elements / dt, "unit": "elements/s", "cores": oracle.num_threads(), "kind": "oracle",
+                "sample": f"first {nseq} of {w.B} sequences of the same workload, one pass, {elements} race elements, "
+                          f"{dt:.2f} s wall"}
+    check = {"sample_sequences": nseq, "token_mismatches_vs_oracle": mism, "accept_len_mismatches_vs_oracle": mism_acc,
+             "oracle_near_tie_rows": near, "mean_accept_len_gpu": float(np.mean(gpu[2]))}
+    return base_out, check
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,168 @@
+/*
+ * libersd -- exponential-race speculative-decoding verification on one AMD MI355X (gfx950).
+ *
+ * What the entry points compute (paper: Section 3 "Exponential Races"; Algorithm 2 for one drafted
+ * token; the sequence extension in Section 3, "an exponential race for every node in the draft
+ * sequence"; Algorithm 5 and Section 2 for trees):
+ *
+ *   For one context, every vocabulary token i gets an exponential e_i ~ Exp(1).  The drafted token is
+ *   the race winner under the draft model, argmin_i e_i / Q(i); the token the target model emits is the
+ *   winner of the SAME race under the target model, argmin_i e_i / P(i).  A drafted token is accepted
+ *   when the two winners agree, and drafted tokens are accepted in order until the first disagreement.
+ *
+ * With Q = softmax(draft_logits / T), P = softmax(target_logits / T) and the monotone map -log named
+ * in Section 3 (Gumbel-max form), argmin_i e_i / p_i = argmax_i ( logit_i / T - ln e_i ): the softmax
+ * normaliser does not depend on i and is never computed.
+ *
+ * Conventions the paper leaves open and this library fixes:
+ *   - e_i = -log1p(-v), v = (x + 1/2) * 2^-32, where x is word (i & 3) of
+ *     Philox4x32-10( counter = (i >> 2, position-or-node index, sequence index b, draft index d),
+ *                    key = (seed & 0xffffffff, seed >> 32) ).
+ *     A caller that decodes several steps passes a fresh seed per step.
+ *   - The winner is decided on scores evaluated in IEEE double precision from the exactly widened
+ *     logit: score = (double)logit / (double)T - ln e_i.  Exactly equal scores go to the lowest token
+ *     index, at every stage of the reduction.
+ *   - Position k of a sequence (the extra token emitted after k accepted drafts, Algorithm 2's second
+ *     returned token) is drawn by a fresh target-only race on target row k.
+ *
+ * Memory: all logits, outputs, `parent` and `workspace` are DEVICE pointers owned by the caller.  The
+ * library allocates nothing, copies nothing to the host and never synchronises: each call enqueues
+ * its kernels on `stream` (a hipStream_t passed as void*, NULL = the default stream) and returns.
+ * Outputs are valid once the stream has completed.  Calls are thread safe as long as concurrent
+ * calls use distinct workspaces.
+ *
+ * Layout: tensors are row-major and contiguous with the vocabulary axis innermost; the draft and the
+ * target tensor have the same element type.  Logit pointers must be 16-byte aligned, int32 outputs
+ * 4-byte aligned, the workspace 16-byte aligned.  V may be any positive value; rows are streamed with
+ * 128-bit loads when V is a multiple of 8 and with element loads otherwise.
+ *
+ * Logit contents: -inf is a legal masked token and never wins unless its whole row is -inf, in which
+ * case token 0 wins.  NaN logits give unspecified tokens (never a fault).
+ *
+ * Errors: every argument error is detected on the host before any HIP call is made and is returned
+ * as a negative status; nothing is enqueued in that case.  ERSD_ERR_HIP reports a failed launch.
+ */
+#ifndef ERSD_H
+#define ERSD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ERSD_F32 = 0,  /* IEEE binary32 logits  */
+    ERSD_BF16 = 1  /* bfloat16 logits       */
+} ersd_dtype;
+
+typedef enum {
+    ERSD_OK = 0,
+    ERSD_ERR_NULL_POINTER = -1,
+    ERSD_ERR_INVALID_ARG = -2,       /* a size < 1, sizes whose products overflow, T not finite or <= 0 */
+    ERSD_ERR_UNSUPPORTED_DTYPE = -3,
+    ERSD_ERR_MISALIGNED = -4,
+    ERSD_ERR_WORKSPACE_TOO_SMALL = -5,
+    ERSD_ERR_HIP = -6
+} ersd_status;
+
+typedef enum { ERSD_VARIANT_SEQUENCE = 0, ERSD_VARIANT_MULTI = 1, ERSD_VARIANT_TREE = 2 } ersd_variant;
+
+/*
+ * Bytes of device workspace the matching verify call needs (partial winners of vocabulary splits).
+ * `m` is ignored for the sequence and tree variants, `k_or_N` is k (sequence, multi) or N (tree).
+ * Returns 0 for invalid sizes.  Pure host computation.
+ */
+size_t ersd_race_workspace_bytes(int variant, int32_t B, int32_t m, int32_t k_or_N, int32_t V, ersd_dtype dt);
+
+/*
+ * Sequence drafting (Section 2 "sequence" strategy verified with the races of Section 3).
+ *   draft_logits  [B, k, V]     logits of the draft model at the k drafted positions
+ *   target_logits [B, k+1, V]   logits of the target model at those positions plus the bonus position
+ *   draft_tokens  [B, k]    out: race winner under the draft model at (b, j)
+ *   target_tokens [B, k+1]  out: winner of the same race under the target model; row k is the bonus race
+ *   accept_len    [B]       out: number of leading positions j < k with draft_tokens == target_tokens.
+ *                           The tokens to emit for sequence b are target_tokens[b, 0 .. accept_len[b]].
+ * Race (b, j) uses counter words (i >> 2, j, b, 0).
+ */
+int ersd_race_verify(const void* draft_logits, const void* target_logits, ersd_dtype dt,
+                     int32_t B, int32_t k, int32_t V, float temperature, uint64_t seed,
+                     int32_t* draft_tokens, int32_t* target_tokens, int32_t* accept_len,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * m independent draft sequences per prompt (a benchmark workload, not a procedure of the paper: the
+ * paper's way to use several alternatives at one context is the first arrivals of ONE race, Section 3).
+ *   draft_logits [B, m, k, V], target_logits [B, m, k+1, V]
+ *   draft_tokens [B, m, k], target_tokens [B, m, k+1], accept_len [B, m] as above per (b, d)
+ *   best_len [B]   out: max over d of accept_len[b, d];  best_draft [B] out: lowest d attaining it
+ * Race (b, d, j) uses counter words (i >> 2, j, b, d).
+ */
+int ersd_race_verify_multi(const void* draft_logits, const void* target_logits, ersd_dtype dt,
+                           int32_t B, int32_t m, int32_t k, int32_t V, float temperature, uint64_t seed,
+                           int32_t* draft_tokens, int32_t* target_tokens, int32_t* accept_len,
+                           int32_t* best_draft, int32_t* best_len,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Draft tree (Section 2 "tree" strategy, walk of Algorithm 5) with one race per node.
+ *   draft_logits, target_logits [B, N, V]   per-node logits
+ *   parent [N] (device, shared by all B): -1 for children of the token-less root (the prompt context),
+ *          otherwise 0 <= parent[n] < n.  Any other value makes node n and its descendants unaccepted.
+ *   draft_tokens, target_tokens [B, N]   out: the two winners of race (b, n), counter words (i >> 2, n, b, 0)
+ *   accept_len  [B]  out: depth (root children have depth 1) of the deepest node all of whose root path
+ *                    agrees; 0 if no root child agrees
+ *   accept_node [B]  out, may be NULL: lowest node index attaining accept_len; -1 if accept_len == 0
+ * A chain-shaped tree gives the sequence variant's tokens and accept_len (without the bonus race).
+ */
+int ersd_race_verify_tree(const void* draft_logits, const void* target_logits, ersd_dtype dt,
+                          int32_t B, int32_t N, int32_t V, const int32_t* parent,
+                          float temperature, uint64_t seed,
+                          int32_t* draft_tokens, int32_t* target_tokens,
+                          int32_t* accept_len, int32_t* accept_node,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The two stages every verify call is made of, for callers that run them apart (a vocabulary-sharded
+ * caller gathers the partial winners between them; a profiler times them separately).
+ *
+ * ersd_race_stage_races runs the races (Section 3) and leaves, in `workspace`, the partial winner of
+ * every vocabulary split of every race and side.  ersd_race_stage_accept combines those partials into
+ * tokens and runs the acceptance step of the variant (first disagreement, best draft, tree walk).
+ * Arguments mean what they mean in the verify call of the same `variant` (ersd_variant; `m` is ignored
+ * unless variant is MULTI, k_or_N is k or N); outputs that the variant does not have (best_draft,
+ * best_len, accept_node, parent) are ignored and may be NULL.  Both calls must be given the same sizes
+ * and workspace; calling them back to back on one stream is exactly the verify call.
+ */
+int ersd_race_stage_races(int variant, const void* draft_logits, const void* target_logits, ersd_dtype dt,
+                          int32_t B, int32_t m, int32_t k_or_N, int32_t V, float temperature, uint64_t seed,
+                          void* workspace, size_t workspace_bytes, void* stream);
+int ersd_race_stage_accept(int variant, int32_t B, int32_t m, int32_t k_or_N, int32_t V, const int32_t* parent,
+                           int32_t* draft_tokens, int32_t* target_tokens, int32_t* accept_len,
+                           int32_t* best_draft, int32_t* best_len, int32_t* accept_node,
+                           const void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Device self-check of the two single-precision bounds the streaming filter relies on, over all 2^32
+ * generator words, against double precision.  counters: DEVICE array of 4 uint64, written as
+ *   [0] words whose cheap upper bound of -log2 e fell below the true value      (must be 0)
+ *   [1] words whose refined log2 e is off by more than 2^-7                    (must be 0)
+ *   [2] largest refinement error, [3] largest upper-bound slack (IEEE fp32 bit patterns)
+ * Enqueues on `stream`; takes a fraction of a second.
+ */
+int ersd_selftest_bounds(uint64_t* counters, void* stream);
+
+/* Host helper: 1 if parent[0..N) (a HOST array) satisfies the tree contract above, else 0. */
+int ersd_tree_validate_host(const int32_t* parent_host, int32_t N);
+
+/* Static text for a status code (never NULL). */
+const char* ersd_status_string(int status);
+
+/* major * 10000 + minor * 100 + patch */
+int ersd_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,265 @@
+"""Thin binding of libersd's C ABI: argument marshalling only.
+
+torch supplies device memory and the current HIP stream; every step of the race runs in the library's
+kernels.  There is no CPU or eager fallback: a missing library or a tensor that is not on the GPU raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libersd.so")
+
+ERSD_F32, ERSD_BF16 = 0, 1
+VARIANT_SEQUENCE, VARIANT_MULTI, VARIANT_TREE = 0, 1, 2
+
+_lib = None
+
+
+class ErsdError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__(f"libersd status {status}: {text}")
+        self.status = status
+
+
+def lib():
+    """Load libersd.so (built in-tree by paper_2504_15475_amd/build.py); fails loudly if it is absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it first (python -m paper_2504_15475_amd.build or __graft_entry__.build())")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, u64, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_uint64, ctypes.c_float, ctypes.c_size_t
+        L.ersd_race_workspace_bytes.argtypes = [ctypes.c_int, i32, i32, i32, i32, ctypes.c_int]
+        L.ersd_race_workspace_bytes.restype = sz
+        L.ersd_race_verify.argtypes = [vp, vp, ctypes.c_int, i32, i32, i32, f32, u64, vp, vp, vp, vp, sz, vp]
+        L.ersd_race_verify.restype = ctypes.c_int
+        L.ersd_race_verify_multi.argtypes = [vp, vp, ctypes.c_int, i32, i32, i32, i32, f32, u64,
+                                             vp, vp, vp, vp, vp, vp, sz, vp]
+        L.ersd_race_verify_multi.restype = ctypes.c_int
+        L.ersd_race_verify_tree.argtypes = [vp, vp, ctypes.c_int, i32, i32, i32, vp, f32, u64,
+                                            vp, vp, vp, vp, vp, sz, vp]
+        L.ersd_race_verify_tree.restype = ctypes.c_int
+        L.ersd_race_stage_races.argtypes = [ctypes.c_int, vp, vp, ctypes.c_int, i32, i32, i32, i32, f32, u64, vp, sz, vp]
+        L.ersd_race_stage_races.restype = ctypes.c_int
+        L.ersd_race_stage_accept.argtypes = [ctypes.c_int, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.ersd_race_stage_accept.restype = ctypes.c_int
+        L.ersd_selftest_bounds.argtypes = [vp, vp]
+        L.ersd_selftest_bounds.restype = ctypes.c_int
+        L.ersd_tree_validate_host.argtypes = [vp, i32]
+        L.ersd_tree_validate_host.restype = ctypes.c_int
+        L.ersd_status_string.argtypes = [ctypes.c_int]
+        L.ersd_status_string.restype = ctypes.c_char_p
+        L.ersd_version.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def status_string(status):
+    return lib().ersd_status_string(int(status)).decode()
+
+
+def version():
+    return lib().ersd_version()
+
+
+def _check(status):
+    if status != 0:
+        raise ErsdError(status, status_string(status))
+
+
+def _dtype_code(t):
+    if t.dtype == torch.float32:
+        return ERSD_F32
+    if t.dtype == torch.bfloat16:
+        return ERSD_BF16
+    raise TypeError(f"logits must be float32 or bfloat16, got {t.dtype}")
+
+
+def _dev(t, name):
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU (libersd has no CPU path)")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def workspace_bytes(variant, B, m, k_or_N, V, dtype_code):
+    return int(lib().ersd_race_workspace_bytes(variant, B, m, k_or_N, V, dtype_code))
+
+
+def _workspace(variant, B, m, k_or_N, V, code, device, workspace):
+    need = workspace_bytes(variant, B, m, k_or_N, V, code)
+    if need == 0:
+        raise ErsdError(-2, status_string(-2))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=device)
+    return workspace, workspace.numel() * workspace.element_size()
+
+
+def race_verify(draft_logits, target_logits, temperature, seed, workspace=None):
+    """Sequence variant.  draft [B,k,V], target [B,k+1,V] -> (draft_tokens [B,k], target_tokens [B,k+1], accept_len [B])."""
+    d, t = _dev(draft_logits, "draft_logits"), _dev(target_logits, "target_logits")
+    code = _dtype_code(d)
+    if _dtype_code(t) != code:
+        raise TypeError("draft and target logits must share a dtype")
+    B, k, V = d.shape
+    if tuple(t.shape) != (B, k + 1, V):
+        raise ValueError(f"target_logits must be [B,k+1,V]=({B},{k + 1},{V}), got {tuple(t.shape)}")
+    dtok = torch.empty((B, k), dtype=torch.int32, device=d.device)
+    ttok = torch.empty((B, k + 1), dtype=torch.int32, device=d.device)
+    acc = torch.empty((B,), dtype=torch.int32, device=d.device)
+    ws, ws_bytes = _workspace(VARIANT_SEQUENCE, B, 1, k, V, code, d.device, workspace)
+    _check(lib().ersd_race_verify(d.data_ptr(), t.data_ptr(), code, B, k, V, float(temperature), int(seed),
+                                  dtok.data_ptr(), ttok.data_ptr(), acc.data_ptr(), ws.data_ptr(), ws_bytes, _stream()))
+    return dtok, ttok, acc
+
+
+def race_verify_multi(draft_logits, target_logits, temperature, seed, workspace=None):
+    """draft [B,m,k,V], target [B,m,k+1,V] -> (draft_tokens, target_tokens, accept_len [B,m], best_draft [B], best_len [B])."""
+    d, t = _dev(draft_logits, "draft_logits"), _dev(target_logits, "target_logits")
+    code = _dtype_code(d)
+    if _dtype_code(t) != code:
+        raise TypeError("draft and target logits must share a dtype")
+    B, m, k, V = d.shape
+    if tuple(t.shape) != (B, m, k + 1, V):
+        raise ValueError(f"target_logits must be [B,m,k+1,V], got {tuple(t.shape)}")
+    dev = d.device
+    dtok = torch.empty((B, m, k), dtype=torch.int32, device=dev)
+    ttok = torch.empty((B, m, k + 1), dtype=torch.int32, device=dev)
+    acc = torch.empty((B, m), dtype=torch.int32, device=dev)
+    bd = torch.empty((B,), dtype=torch.int32, device=dev)
+    bl = torch.empty((B,), dtype=torch.int32, device=dev)
+    ws, ws_bytes = _workspace(VARIANT_MULTI, B, m, k, V, code, dev, workspace)
+    _check(lib().ersd_race_verify_multi(d.data_ptr(), t.data_ptr(), code, B, m, k, V, float(temperature), int(seed),
+                                        dtok.data_ptr(), ttok.data_ptr(), acc.data_ptr(), bd.data_ptr(), bl.data_ptr(),
+                                        ws.data_ptr(), ws_bytes, _stream()))
+    return dtok, ttok, acc, bd, bl
+
+
+def race_verify_tree(draft_logits, target_logits, parent, temperature, seed, workspace=None):
+    """draft, target [B,N,V]; parent int32 [N] on the GPU -> (draft_tokens, target_tokens [B,N], accept_len [B], accept_node [B])."""
+    d, t = _dev(draft_logits, "draft_logits"), _dev(target_logits, "target_logits")
+    p = _dev(parent, "parent")
+    code = _dtype_code(d)
+    if _dtype_code(t) != code:
+        raise TypeError("draft and target logits must share a dtype")
+    B, N, V = d.shape
+    if tuple(t.shape) != (B, N, V):
+        raise ValueError(f"target_logits must be [B,N,V], got {tuple(t.shape)}")
+    if p.dtype != torch.int32 or tuple(p.shape) != (N,):
+        raise ValueError("parent must be int32 [N]")
+    dev = d.device
+    dtok = torch.empty((B, N), dtype=torch.int32, device=dev)
+    ttok = torch.empty((B, N), dtype=torch.int32, device=dev)
+    acc = torch.empty((B,), dtype=torch.int32, device=dev)
+    node = torch.empty((B,), dtype=torch.int32, device=dev)
+    ws, ws_bytes = _workspace(VARIANT_TREE, B, 1, N, V, code, dev, workspace)
+    _check(lib().ersd_race_verify_tree(d.data_ptr(), t.data_ptr(), code, B, N, V, p.data_ptr(), float(temperature),
+                                       int(seed), dtok.data_ptr(), ttok.data_ptr(), acc.data_ptr(), node.data_ptr(),
+                                       ws.data_ptr(), ws_bytes, _stream()))
+    return dtok, ttok, acc, node
+
+
+class PreparedVerify:
+    """One verify call with its outputs and workspace allocated up front, so that repeated launches (a serving
+    loop, the benchmark) do no allocation and little Python work.  `run()` is the variant's verify entry point;
+    `run_stages(mid_event)` issues the two stages separately and records `mid_event` between them."""
+
+    def __init__(self, variant, draft_logits, target_logits, temperature, seed, parent=None):
+        d, t = _dev(draft_logits, "draft_logits"), _dev(target_logits, "target_logits")
+        self.code = _dtype_code(d)
+        if _dtype_code(t) != self.code:
+            raise TypeError("draft and target logits must share a dtype")
+        self.variant = variant
+        dev = d.device
+        if variant == VARIANT_SEQUENCE:
+            B, k, V = d.shape
+            m, kn, tshape = 1, k, (B, k + 1, V)
+            shapes = ((B, k), (B, k + 1), (B,))
+        elif variant == VARIANT_MULTI:
+            B, m, k, V = d.shape
+            kn, tshape = k, (B, m, k + 1, V)
+            shapes = ((B, m, k), (B, m, k + 1), (B, m))
+        else:
+            B, N, V = d.shape
+            m, kn, tshape = 1, N, (B, N, V)
+            shapes = ((B, N), (B, N), (B,))
+            if parent is None or parent.dtype != torch.int32 or tuple(parent.shape) != (N,):
+                raise ValueError("parent must be int32 [N]")
+            _dev(parent, "parent")
+        if tuple(t.shape) != tshape:
+            raise ValueError(f"target_logits must have shape {tshape}, got {tuple(t.shape)}")
+        self.B, self.m, self.kn, self.V = B, m, kn, V
+        self.draft, self.target, self.parent = d, t, parent
+        self.temperature, self.seed = float(temperature), int(seed)
+        i32 = dict(dtype=torch.int32, device=dev)
+        self.draft_tokens = torch.empty(shapes[0], **i32)
+        self.target_tokens = torch.empty(shapes[1], **i32)
+        self.accept_len = torch.empty(shapes[2], **i32)
+        self.best_draft = torch.empty((B,), **i32) if variant == VARIANT_MULTI else None
+        self.best_len = torch.empty((B,), **i32) if variant == VARIANT_MULTI else None
+        self.accept_node = torch.empty((B,), **i32) if variant == VARIANT_TREE else None
+        self.workspace, self.ws_bytes = _workspace(variant, B, m, kn, V, self.code, dev, None)
+        self._p = lambda x: None if x is None else x.data_ptr()
+
+    def outputs(self):
+        if self.variant == VARIANT_SEQUENCE:
+            return self.draft_tokens, self.target_tokens, self.accept_len
+        if self.variant == VARIANT_MULTI:
+            return self.draft_tokens, self.target_tokens, self.accept_len, self.best_draft, self.best_len
+        return self.draft_tokens, self.target_tokens, self.accept_len, self.accept_node
+
+    def run(self):
+        L, p, st = lib(), self._p, _stream()
+        if self.variant == VARIANT_SEQUENCE:
+            rc = L.ersd_race_verify(p(self.draft), p(self.target), self.code, self.B, self.kn, self.V, self.temperature,
+                                    self.seed, p(self.draft_tokens), p(self.target_tokens), p(self.accept_len),
+                                    p(self.workspace), self.ws_bytes, st)
+        elif self.variant == VARIANT_MULTI:
+            rc = L.ersd_race_verify_multi(p(self.draft), p(self.target), self.code, self.B, self.m, self.kn, self.V,
+                                          self.temperature, self.seed, p(self.draft_tokens), p(self.target_tokens),
+                                          p(self.accept_len), p(self.best_draft), p(self.best_len), p(self.workspace),
+                                          self.ws_bytes, st)
+        else:
+            rc = L.ersd_race_verify_tree(p(self.draft), p(self.target), self.code, self.B, self.kn, self.V,
+                                         p(self.parent), self.temperature, self.seed, p(self.draft_tokens),
+                                         p(self.target_tokens), p(self.accept_len), p(self.accept_node),
+                                         p(self.workspace), self.ws_bytes, st)
+        _check(rc)
+        return self.outputs()
+
+    def run_stages(self, mid_event=None):
+        L, p, st = lib(), self._p, _stream()
+        _check(L.ersd_race_stage_races(self.variant, p(self.draft), p(self.target), self.code, self.B, self.m, self.kn,
+                                       self.V, self.temperature, self.seed, p(self.workspace), self.ws_bytes, st))
+        if mid_event is not None:
+            mid_event.record()
+        _check(L.ersd_race_stage_accept(self.variant, self.B, self.m, self.kn, self.V, p(self.parent),
+                                        p(self.draft_tokens), p(self.target_tokens), p(self.accept_len),
+                                        p(self.best_draft), p(self.best_len), p(self.accept_node), p(self.workspace),
+                                        self.ws_bytes, st))
+        return self.outputs()
+
+
+def selftest_bounds(device="cuda"):
+    """Run the device self-check of the filter's fp32 bounds -> dict(bad_upper, bad_refine, max_refine_err, max_upper_slack)."""
+    c = torch.zeros(4, dtype=torch.int64, device=device)
+    _check(lib().ersd_selftest_bounds(c.data_ptr(), _stream()))
+    torch.cuda.synchronize()
+    h = c.cpu()
+    as_float = lambda v: torch.tensor([int(v)], dtype=torch.int32).view(torch.float32).item()
+    return dict(bad_upper=int(h[0]), bad_refine=int(h[1]), max_refine_err=as_float(h[2]), max_upper_slack=as_float(h[3]))
+
+
+def tree_validate_host(parent):
+    """parent: host int32 array/tensor -> bool (the tree contract of ersd_race_verify_tree)."""
+    import numpy as np
+    a = np.ascontiguousarray(np.asarray(parent, dtype=np.int32))
+    return bool(lib().ersd_tree_validate_host(a.ctypes.data, a.shape[0]))

@@ -1,0 +1,84 @@
+"""Comparison of GPU results with the oracle's, to the bar: bit-exact tokens and accept lengths, except at rows
+the oracle flags as near-ties (top-2 scores within 1e-6 relative, not exactly equal), where the GPU token must be
+one of the oracle's tied candidates.  Exempted rows are counted and returned."""
+import numpy as np
+
+
+def _np(t):
+    return t.detach().cpu().numpy() if hasattr(t, "detach") else np.asarray(t)
+
+
+def compare_tokens(name, gpu_tok, info, oracle_mod, row_fetch, temperature, seed, counters):
+    """gpu_tok, info: same shape [..]; row_fetch(index_tuple) -> host row; counters(index_tuple) -> (c1, c2, c3)."""
+    gpu_tok = _np(gpu_tok)
+    exempt = 0
+    bad = np.argwhere(gpu_tok != info["token"])
+    for ix in map(tuple, bad):
+        r = info[ix]
+        assert r["near_tie"] == 1 and r["exact_tie"] == 0, (
+            f"{name}{ix}: gpu {gpu_tok[ix]} != oracle {r['token']} with score gap {r['s1'] - r['s2']:.3e} (not a near-tie)")
+        c1, c2, c3 = counters(ix)
+        cand, n = oracle_mod.row_candidates(row_fetch(ix), temperature, seed, c1, c2, c3)
+        assert gpu_tok[ix] in cand.tolist(), f"{name}{ix}: gpu token {gpu_tok[ix]} not among near-tie candidates {cand}"
+        exempt += 1
+    return exempt
+
+
+def leading_agreement(d, t):
+    """d [..., k], t [..., k+1] -> run of leading equal positions."""
+    eq = d == t[..., : d.shape[-1]]
+    return np.where(eq.all(-1), d.shape[-1], np.argmin(eq, axis=-1)).astype(np.int32)
+
+
+def check_sequence(gpu, ora, oracle_mod, draft_host, target_host, T, seed, multi=False):
+    """gpu: tuple from the binding; ora: oracle dict with infos.  Returns number of exempted rows."""
+    dtok, ttok, acc = (_np(x) for x in gpu[:3])
+    if multi:
+        cnt_d = cnt_t = lambda ix: (ix[2], ix[0], ix[1])
+    else:
+        cnt_d = cnt_t = lambda ix: (ix[1], ix[0], 0)
+    ex = compare_tokens("draft", dtok, ora["draft_info"], oracle_mod, lambda ix: draft_host[ix], T, seed, cnt_d)
+    ex += compare_tokens("target", ttok, ora["target_info"], oracle_mod, lambda ix: target_host[ix], T, seed, cnt_t)
+    # accept lengths: always the leading agreement of the GPU's own tokens, and the oracle's wherever tokens agree
+    assert np.array_equal(acc, leading_agreement(dtok, ttok))
+    if ex == 0:
+        assert np.array_equal(acc, ora["accept_len"])
+    if multi:
+        bd, bl = _np(gpu[3]), _np(gpu[4])
+        assert np.array_equal(bl, acc.max(-1)) and np.array_equal(bd, acc.argmax(-1))
+        if ex == 0:
+            assert np.array_equal(bl, ora["best_len"]) and np.array_equal(bd, ora["best_draft"])
+    return ex
+
+
+def tree_accept_reference(dtok, ttok, parent):
+    """Plain ancestor walk on token arrays (host), for self-consistency of the GPU's accept outputs."""
+    B, N = dtok.shape
+    acc = np.zeros(B, dtype=np.int32)
+    node = np.full(B, -1, dtype=np.int32)
+    for b in range(B):
+        depth = np.zeros(N, dtype=np.int32)
+        for n in range(N):
+            p = parent[n]
+            if dtok[b, n] != ttok[b, n] or p < -1 or p >= n:
+                continue
+            if p == -1:
+                depth[n] = 1
+            elif depth[p] > 0:
+                depth[n] = depth[p] + 1
+        if depth.max() > 0:
+            acc[b] = depth.max()
+            node[b] = int(np.argmax(depth))
+    return acc, node
+
+
+def check_tree(gpu, ora, oracle_mod, draft_host, target_host, parent_host, T, seed):
+    dtok, ttok, acc, node = (_np(x) for x in gpu)
+    cnt = lambda ix: (ix[1], ix[0], 0)
+    ex = compare_tokens("draft", dtok, ora["draft_info"], oracle_mod, lambda ix: draft_host[ix], T, seed, cnt)
+    ex += compare_tokens("target", ttok, ora["target_info"], oracle_mod, lambda ix: target_host[ix], T, seed, cnt)
+    ra, rn = tree_accept_reference(dtok, ttok, np.asarray(parent_host))
+    assert np.array_equal(acc, ra) and np.array_equal(node, rn)
+    if ex == 0:
+        assert np.array_equal(acc, ora["accept_len"]) and np.array_equal(node, ora["accept_node"])
+    return ex

@@ -1,0 +1,131 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports what include/ersd.h declares,
+and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2504_15475_amd import race
+    return race.lib()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "ersd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ersd_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = declared_functions()
+    assert {"ersd_race_verify", "ersd_race_verify_multi", "ersd_race_verify_tree", "ersd_race_workspace_bytes",
+            "ersd_status_string", "ersd_version", "ersd_tree_validate_host", "ersd_selftest_bounds"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_version_and_status_strings(L):
+    assert L.ersd_version() >= 100
+    seen = set()
+    for s in range(0, -7, -1):
+        txt = L.ersd_status_string(s)
+        assert txt and txt not in seen
+        seen.add(txt)
+    assert L.ersd_status_string(-99) == b"unknown status"
+
+
+FAKE = 0x10000  # non-null, 16-byte aligned; never dereferenced because every call below fails validation first
+
+
+def seq_call(L, d=FAKE, t=FAKE, dt=0, B=1, k=2, V=64, T=1.0, seed=0, o1=FAKE, o2=FAKE, o3=FAKE, ws=FAKE, wsb=1 << 30):
+    return L.ersd_race_verify(d, t, dt, B, k, V, T, seed, o1, o2, o3, ws, wsb, None)
+
+
+def test_sequence_argument_errors(L):
+    assert seq_call(L, d=None) == -1 and seq_call(L, t=None) == -1
+    assert seq_call(L, o1=None) == -1 and seq_call(L, o2=None) == -1 and seq_call(L, o3=None) == -1
+    assert seq_call(L, ws=None) == -1
+    assert seq_call(L, dt=2) == -3 and seq_call(L, dt=-1) == -3
+    for T in (0.0, -1.0, float("nan"), float("inf")):
+        assert seq_call(L, T=T) == -2
+    assert seq_call(L, B=0) == -2 and seq_call(L, k=0) == -2 and seq_call(L, V=0) == -2 and seq_call(L, B=-3) == -2
+    assert seq_call(L, k=2**31 - 1) == -2                     # k + 1 would overflow
+    assert seq_call(L, B=2**20, k=2**12, V=8) == -2           # too many rows for the grid
+    assert seq_call(L, d=FAKE + 4) == -4 and seq_call(L, t=FAKE + 8) == -4 and seq_call(L, ws=FAKE + 2) == -4
+    assert seq_call(L, wsb=8) == -5
+
+
+def test_multi_and_tree_argument_errors(L):
+    def multi(**kw):
+        a = dict(d=FAKE, t=FAKE, dt=1, B=2, m=3, k=2, V=64, T=1.0, seed=0, o=[FAKE] * 5, ws=FAKE, wsb=1 << 30)
+        a.update(kw)
+        return L.ersd_race_verify_multi(a["d"], a["t"], a["dt"], a["B"], a["m"], a["k"], a["V"], a["T"], a["seed"],
+                                        *a["o"], a["ws"], a["wsb"], None)
+    assert multi(m=0) == -2 and multi(T=0.0) == -2 and multi(d=None) == -1 and multi(wsb=0) == -5
+    for i in range(5):
+        o = [FAKE] * 5
+        o[i] = None
+        assert multi(o=o) == -1
+
+    def tree(**kw):
+        a = dict(d=FAKE, t=FAKE, dt=1, B=2, N=5, V=64, parent=FAKE, T=1.0, seed=0, o=[FAKE] * 4, ws=FAKE, wsb=1 << 30)
+        a.update(kw)
+        return L.ersd_race_verify_tree(a["d"], a["t"], a["dt"], a["B"], a["N"], a["V"], a["parent"], a["T"],
+                                       a["seed"], *a["o"], a["ws"], a["wsb"], None)
+    assert tree(parent=None) == -1 and tree(N=0) == -2 and tree(T=-2.0) == -2 and tree(wsb=1) == -5
+    assert tree(o=[FAKE, FAKE, None, FAKE]) == -1
+    assert L.ersd_selftest_bounds(None, None) == -1
+
+
+def test_workspace_bytes(L):
+    wb = L.ersd_race_workspace_bytes
+    assert wb(0, 1, 1, 4, 32000, 0) > 0
+    assert wb(0, 0, 1, 4, 32000, 0) == 0 and wb(3, 1, 1, 4, 32000, 0) == 0 and wb(0, 1, 1, 4, 32000, 5) == 0
+    # enough for one 16-byte partial per (row, side); more rows never need less
+    assert wb(0, 64, 1, 8, 128256, 1) >= 64 * 9 * 2 * 16
+    assert wb(1, 32, 8, 8, 128256, 1) >= 32 * 8 * 9 * 2 * 16
+    assert wb(2, 16, 1, 64, 256000, 1) >= 16 * 64 * 2 * 16
+    # the documented size is sufficient and one byte less is rejected (checked before any device work)
+    need = wb(0, 2, 1, 3, 4096, 0)
+    assert seq_call(L, B=2, k=3, V=4096, wsb=need - 1) == -5
+
+
+def test_tree_validate_host():
+    from paper_2504_15475_amd import race
+    assert race.tree_validate_host(np.array([-1, 0, 0, 1, -1], dtype=np.int32))
+    assert not race.tree_validate_host(np.array([-1, 1], dtype=np.int32))       # self / forward reference
+    assert not race.tree_validate_host(np.array([-2, 0], dtype=np.int32))
+    assert not race.tree_validate_host(np.array([0], dtype=np.int32))
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    from paper_2504_15475_amd import race
+    d = torch.zeros(1, 2, 8)
+    t = torch.zeros(1, 3, 8)
+    with pytest.raises(ValueError):
+        race.race_verify(d, t, 1.0, 0)
+
+
+def test_workload_generators_are_seeded_and_shaped():
+    import torch
+    from paper_2504_15475_amd import workloads as wl
+    assert [w.race_elements for w in wl.WORKLOADS] == [288000, 139542528, 1284636672, 558170112, 524288000]
+    small = wl.shrink(wl.WORKLOADS[1], B=2, k=3, V=1024)
+    a, b = wl.make_inputs(small), wl.make_inputs(small)
+    assert a["draft"].dtype == torch.bfloat16 and tuple(a["target"].shape) == (2, 4, 1024)
+    assert torch.equal(a["target"], b["target"]) and torch.equal(a["draft"], b["draft"])
+    t = wl.shrink(wl.WORKLOADS[4], B=2, N=64, V=256, level_sizes=(4, 8, 12, 14, 14, 12))
+    p = wl.tree_parents(t)
+    from paper_2504_15475_amd import race
+    assert race.tree_validate_host(p) and (p[:4] == -1).all() and p.max() < 63
+    m = wl.make_inputs(wl.shrink(wl.WORKLOADS[3], B=2, m=3, k=2, V=512))
+    assert tuple(m["draft"].shape) == (2, 3, 2, 512) and tuple(m["target"].shape) == (2, 3, 3, 512)
+    c2 = wl.make_inputs(wl.shrink(wl.WORKLOADS[2], B=2, k=2, V=4096))
+    assert c2["target"].dtype == torch.float32 and float(c2["target"].max()) > 12.0     # boosted tokens present
