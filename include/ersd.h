@@ -70,7 +70,7 @@ typedef enum {
 typedef enum { ERSD_VARIANT_SEQUENCE = 0, ERSD_VARIANT_MULTI = 1, ERSD_VARIANT_TREE = 2 } ersd_variant;
 
 /*
- * Bytes of device workspace the matching verify call needs (partial winners of vocabulary splits).
+ * Bytes of device workspace the matching verify call needs (surviving candidates of row segments).
  * `m` is ignored for the sequence and tree variants, `k_or_N` is k (sequence, multi) or N (tree).
  * Returns 0 for invalid sizes.  Pure host computation.
  */
@@ -127,21 +127,35 @@ int ersd_race_verify_tree(const void* draft_logits, const void* target_logits, e
  * The two stages every verify call is made of, for callers that run them apart (a vocabulary-sharded
  * caller gathers the partial winners between them; a profiler times them separately).
  *
- * ersd_race_stage_races runs the races (Section 3) and leaves, in `workspace`, the partial winner of
- * every vocabulary split of every race and side.  ersd_race_stage_accept combines those partials into
- * tokens and runs the acceptance step of the variant (first disagreement, best draft, tree walk).
+ * ersd_race_stage_races runs the races (Section 3) and leaves, in `workspace`, for every race, side and
+ * row segment the few tokens that can still be the winner.  ersd_race_stage_accept decides each row's
+ * winner among them (in double precision where single precision cannot tell) and runs the acceptance
+ * step of the variant (first disagreement, best draft, tree walk).
  * Arguments mean what they mean in the verify call of the same `variant` (ersd_variant; `m` is ignored
  * unless variant is MULTI, k_or_N is k or N); outputs that the variant does not have (best_draft,
- * best_len, accept_node, parent) are ignored and may be NULL.  Both calls must be given the same sizes
- * and workspace; calling them back to back on one stream is exactly the verify call.
+ * best_len, accept_node, parent) are ignored and may be NULL.  Both calls must be given the same sizes,
+ * element type and workspace; calling them back to back on one stream is exactly the verify call.
  */
 int ersd_race_stage_races(int variant, const void* draft_logits, const void* target_logits, ersd_dtype dt,
                           int32_t B, int32_t m, int32_t k_or_N, int32_t V, float temperature, uint64_t seed,
                           void* workspace, size_t workspace_bytes, void* stream);
-int ersd_race_stage_accept(int variant, int32_t B, int32_t m, int32_t k_or_N, int32_t V, const int32_t* parent,
+int ersd_race_stage_accept(int variant, ersd_dtype dt, int32_t B, int32_t m, int32_t k_or_N, int32_t V,
+                           float temperature, const int32_t* parent,
                            int32_t* draft_tokens, int32_t* target_tokens, int32_t* accept_len,
                            int32_t* best_draft, int32_t* best_len, int32_t* accept_node,
                            const void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Host-only description of how a job is cut into equal shares for `blocks` workgroups (1..4096): every
+ * row is a run of 8-token groups, rows are laid end to end, and share b covers the global group indices
+ * [block_start[b], block_start[b+1]).  A row's partial winners are written by the workgroups
+ * row_first[r] .. row_last[r], one slot each, at most *out_nslot of them.
+ *   out_G, out_nslot: never NULL.  block_start: NULL or [G + 1] (G <= blocks).  row_first, row_last: both
+ *   NULL or both [rows], rows = B * m * (k + 1) or B * N.  All HOST arrays.  No device work is done.
+ */
+int ersd_plan_describe_host(int variant, int32_t B, int32_t m, int32_t k_or_N, int32_t V, uint32_t blocks,
+                            uint32_t* out_G, uint32_t* out_nslot, uint64_t* block_start,
+                            uint32_t* row_first, uint32_t* row_last);
 
 /*
  * Device self-check of the two single-precision bounds the streaming filter relies on, over all 2^32

@@ -12,18 +12,24 @@
 //             of the row maximum.
 //   refine  : for those few tokens an fp32 score with a proven error margin, using v_log_f32; tokens
 //             that can still be the maximum are appended to a candidate list in LDS and raise tau.
-//   exact   : after the stream, the candidates (a few dozen per row) are scored in fp64 exactly as the
-//             definition says and reduced with the (score, lowest index) order.
+//   survive : when a row segment has been streamed, only candidates whose fp32 interval still reaches the
+//             final tau survive (usually one); they are handed on as (index, logit, word) records.
+//   exact   : the finishing kernel gathers a row's survivors from all its segments.  If one fp32 interval
+//             lies above all others that token wins; otherwise the contenders are scored in fp64 exactly
+//             as the definition says and reduced with the (score, lowest index) order.
 //
 // Since tau never exceeds the true row maximum and the bounds are one-sided, the true winner (and every
-// token tied with it) is always among the candidates, so the result is the fp64 argmax.
+// token tied with it) is always among the survivors, so the result is the fp64 argmax.
 //
-// Vocabulary splits: a row may be cut into `nsplit` chunks handled by different workgroups; each writes
-// one (score, index) partial per side, combined in index order by the finishing kernel, which also
-// computes the accept lengths (first-mismatch scan, best draft, tree ancestor walk).
+// Work distribution: all rows are laid end to end in units of 8-token groups (a pair row weighs more than
+// a target-only row) and cut into G equal shares, one per resident workgroup, so that every compute unit
+// finishes at the same time whatever the shape.  A share is a list of row segments; each segment leaves
+// its survivors per side in the workspace, and the finishing kernel resolves each row before it computes
+// the accept lengths (first-mismatch scan, best draft, tree ancestor walk).
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdint>
 #include <cstdlib>
@@ -34,33 +40,92 @@
 namespace {
 
 constexpr int kThreads = 256;                       // 4 wavefronts per workgroup
-constexpr int kTokPerThread = 8;                    // two Philox calls, 16 B of bf16 / 32 B of fp32 per side
-constexpr int kTokPerIter = kThreads * kTokPerThread;
-constexpr int kListCap = 1024;                      // candidate slots per side per workgroup
-constexpr int kMaxSplit = 64;
+constexpr int kGroup = 8;                           // tokens a lane filters at a time: two Philox calls
+constexpr int kListCap = 512;                       // candidate slots per side per workgroup
 constexpr int kWave = 64;
+constexpr int kWaves = kThreads / kWave;
+constexpr uint32_t kWPair = 5, kWSingle = 3;        // relative cost of one group in a pair row / target-only row
+constexpr uint64_t kMinQuota = 64 * kWPair * 16;    // cost units a workgroup gets at least (16 pair iterations of a wave)
+constexpr uint32_t kMaxBlocks = 256 * 16;           // upper bound of resident workgroups, for workspace sizing
 
 constexpr uint32_t kPhiloxM0 = 0xD2511F53u, kPhiloxM1 = 0xCD9E8D57u;
 constexpr uint32_t kPhiloxW0 = 0x9E3779B9u, kPhiloxW1 = 0xBB67AE85u;
 
-struct Partial {
-    double score;
+constexpr int kMaxSurvivors = 4;
+
+// What a row segment hands to the finishing kernel for one side: the tokens that can still be the row maximum.
+struct Cand {
     int32_t idx;
-    int32_t pad;
+    uint32_t word;   // the token's Philox word
+    float logit;
+    float s2;        // fp32 score in log2 units, error at most refine_err(s2)
 };
+struct SegOut {
+    int32_t count;   // 0 = no finite score in the segment
+    int32_t pad[3];
+    Cand c[kMaxSurvivors];
+};
+
+// Balanced partition of the concatenated rows (in 8-token groups) over G workgroups.  Shared by the race
+// kernel (which part is mine, which slot do I write) and the finishing kernel (which slots does a row have).
+struct Part {
+    uint64_t U;           // total cost units
+    uint64_t Us;          // cost units per sequence
+    uint64_t pair_units;  // cost units of the pair rows of one sequence
+    uint64_t rows;        // target rows = races
+    uint32_t V8;          // groups per row
+    uint32_t kd, kt;      // draft rows / target rows per sequence
+    uint32_t G;           // workgroups
+    uint32_t nslot;       // partial slots per (row, side)
+};
+
+__host__ __device__ inline uint64_t part_unit_to_pos(const Part& p, uint64_t u) {
+    if (u >= p.U) return p.rows * p.V8;
+    const uint64_t seq = u / p.Us, rem = u % p.Us;
+    uint64_t row, grp;
+    if (rem < p.pair_units) {
+        row = rem / ((uint64_t)kWPair * p.V8);
+        grp = (rem % ((uint64_t)kWPair * p.V8)) / kWPair;
+    } else {
+        const uint64_t r2 = rem - p.pair_units;
+        row = p.kd + r2 / ((uint64_t)kWSingle * p.V8);
+        grp = (r2 % ((uint64_t)kWSingle * p.V8)) / kWSingle;
+    }
+    return (seq * p.kt + row) * p.V8 + grp;
+}
+// first group (global index) of workgroup b's share; b == G gives the end
+__host__ __device__ inline uint64_t part_start_pos(const Part& p, uint32_t b) {
+    return part_unit_to_pos(p, (uint64_t)b * p.U / p.G);
+}
+__host__ __device__ inline uint64_t part_row_unit(const Part& p, uint64_t row, uint32_t* w) {
+    const uint64_t seq = row / p.kt;
+    const uint32_t j = (uint32_t)(row % p.kt);
+    *w = j < p.kd ? kWPair : kWSingle;
+    return seq * p.Us + (j < p.kd ? (uint64_t)j * kWPair * p.V8 : p.pair_units + (uint64_t)(j - p.kd) * kWSingle * p.V8);
+}
+// workgroup that holds the first group of `row` (largest b whose share starts at or before it)
+__host__ __device__ inline uint32_t part_first_block(const Part& p, uint64_t row) {
+    uint32_t w;
+    const uint64_t u0 = part_row_unit(p, row, &w);
+    return (uint32_t)(((u0 + w) * p.G - 1) / p.U);
+}
+// workgroup that holds the last group of `row`
+__host__ __device__ inline uint32_t part_last_block(const Part& p, uint64_t row) {
+    uint32_t w;
+    const uint64_t u1 = part_row_unit(p, row, &w) + (uint64_t)w * p.V8;
+    return (uint32_t)((u1 * p.G - 1) / p.U);
+}
 
 struct RaceArgs {
     const char* draft;
     const char* target;
-    Partial* partials;  // [row][side][split]
+    SegOut* out;        // [row][side][slot]
+    Part part;
     int32_t V;
-    int32_t kd;      // draft rows per sequence (k, or N for a tree)
-    int32_t kt;      // target rows per sequence (k + 1, or N)
-    int32_t m;       // drafts per prompt
-    int32_t nsplit;
-    int32_t chunk;   // tokens per split, a multiple of kTokPerIter
+    int32_t m;          // drafts per prompt
     uint32_t key0, key1;
-    float c2;        // log2(e) / T
+    float c2;           // log2(e) / T
+    int32_t exhaustive; // score every token in fp64 (reference path for tests)
     double T;
 };
 
@@ -97,83 +162,49 @@ __device__ __forceinline__ float widen_elem(const char* row, int dt, int32_t i) 
     return __uint_as_float(bits);
 }
 
-__device__ __forceinline__ double exact_score_at(const char* row, int dt, int32_t i, const RaceArgs& a,
-                                                 uint32_t c1, uint32_t c2, uint32_t c3) {
-    uint32_t w[4];
-    philox4x32_10((uint32_t)i >> 2, c1, c2, c3, a.key0, a.key1, w);
-    return exact_score(widen_elem(row, dt, i), a.T, w[i & 3]);
-}
-
 // (score, index) order: larger score first, then lower index.
 __device__ __forceinline__ bool better(double s, int32_t i, double bs, int32_t bi) {
     return s > bs || (s == bs && i < bi);
 }
 
-// Workgroup argmax; every thread passes its own best (idx < 0 = none).  Result valid in thread 0.
-__device__ void block_argmax(double& s, int32_t& i, double* lds_s, int32_t* lds_i) {
+__device__ __forceinline__ void wave_argmax(double& s, int32_t& i) {
 #pragma unroll
     for (int off = kWave / 2; off > 0; off >>= 1) {
         const double os = __shfl_xor(s, off, kWave);
         const int32_t oi = __shfl_xor(i, off, kWave);
         if (oi >= 0 && (i < 0 || better(os, oi, s, i))) { s = os; i = oi; }
     }
-    const int wave = threadIdx.x / kWave;
-    if ((threadIdx.x & (kWave - 1)) == 0) { lds_s[wave] = s; lds_i[wave] = i; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        for (int w = 1; w < kThreads / kWave; ++w)
-            if (lds_i[w] >= 0 && (i < 0 || better(lds_s[w], lds_i[w], s, i))) { s = lds_s[w]; i = lds_i[w]; }
-    }
-    __syncthreads();
 }
 
-// Row geometry shared by both race kernels.
-struct RowCtx {
+// One row segment handled by one workgroup.
+struct Seg {
     const char* qrow;  // draft row or nullptr (bonus position)
     const char* prow;  // target row
     uint32_t c1, c2, c3;
-    int32_t begin, end;  // token range of this split
-    int64_t row;
-    int32_t split;
+    int32_t begin, end;  // token range, begin a multiple of 8
+    uint64_t row;
+    uint32_t slot;
 };
 
-template <int DT>
-__device__ __forceinline__ RowCtx make_ctx(const RaceArgs& a) {
-    RowCtx c;
-    const int64_t blk = blockIdx.x;
-    c.split = (int32_t)(blk % a.nsplit);
-    c.row = blk / a.nsplit;                  // target row index = seq * kt + j
-    const int64_t seq = c.row / a.kt;        // b * m + d
-    const int32_t j = (int32_t)(c.row % a.kt);
-    const size_t es = DT == ERSD_F32 ? 4 : 2;
-    c.prow = a.target + (size_t)c.row * (size_t)a.V * es;
-    c.qrow = j < a.kd ? a.draft + (size_t)(seq * a.kd + j) * (size_t)a.V * es : nullptr;
-    c.c1 = (uint32_t)j;
-    c.c2 = (uint32_t)(seq / a.m);
-    c.c3 = (uint32_t)(seq % a.m);
-    c.begin = c.split * a.chunk;
-    const int64_t e = (int64_t)c.begin + a.chunk;
-    c.end = e < a.V ? (int32_t)e : a.V;
-    return c;
-}
+struct Lds {
+    int32_t tau[2];      // ordered-int encoding of the workgroup's lower bound, per side
+    int32_t count[2];    // candidates appended (may exceed kListCap: overflow)
+    int32_t idx[2][kListCap];
+    uint32_t word[2][kListCap];
+    float logit[2][kListCap];
+    int32_t nsurv[2];
+    int32_t surv[2][kMaxSurvivors];  // list positions of the survivors
+    double red_s[kWaves];
+    int32_t red_i[kWaves];
+};
 
-__device__ __forceinline__ void store_partial(const RaceArgs& a, const RowCtx& c, int side, double s, int32_t i) {
-    Partial p;
-    p.score = s;
-    p.idx = i;
-    p.pad = 0;
-    a.partials[((size_t)c.row * 2 + side) * a.nsplit + c.split] = p;
-}
-
-// Exact scan of one side of a split: every token scored in fp64.  Used by the reference kernel and as the
-// fallback when a candidate list overflows.
+// Exact scan of one side of a segment: every token scored in fp64.  The reference path, and the fallback when
+// a candidate list overflows.  Waves 0-1 take side 0, waves 2-3 side 1 (lane best only; reduced by the caller).
 template <int DT>
-__device__ void exhaustive_side(const RaceArgs& a, const RowCtx& c, const char* row, int side,
-                                double* lds_s, int32_t* lds_i) {
-    double bs = -INFINITY;
-    int32_t bi = -1;
-    const int32_t g0 = c.begin >> 2, g1 = (c.end + 3) >> 2;  // c.begin is a multiple of 4
-    for (int32_t g = g0 + (int32_t)threadIdx.x; g < g1; g += kThreads) {
+__device__ void exhaustive_half(const RaceArgs& a, const Seg& c, const char* row, int half_tid, double& bs,
+                                int32_t& bi) {
+    const int32_t g0 = c.begin >> 2, g1 = (c.end + 3) >> 2;
+    for (int32_t g = g0 + half_tid; g < g1; g += kThreads / 2) {
         uint32_t w[4];
         philox4x32_10((uint32_t)g, c.c1, c.c2, c.c3, a.key0, a.key1, w);
 #pragma unroll
@@ -185,46 +216,44 @@ __device__ void exhaustive_side(const RaceArgs& a, const RowCtx& c, const char* 
             }
         }
     }
-    block_argmax(bs, bi, lds_s, lds_i);
-    if (threadIdx.x == 0) store_partial(a, c, side, bs, bi);
 }
 
-template <int DT>
-__global__ void __launch_bounds__(kThreads) race_exhaustive_kernel(RaceArgs a) {
-    __shared__ double lds_s[kThreads / kWave];
-    __shared__ int32_t lds_i[kThreads / kWave];
-    const RowCtx c = make_ctx<DT>(a);
-    if (c.qrow) exhaustive_side<DT>(a, c, c.qrow, 0, lds_s, lds_i);
-    exhaustive_side<DT>(a, c, c.prow, 1, lds_s, lds_i);
-}
-
-// ------------------------------------------------------------------------------------------ filtered kernel
+// ------------------------------------------------------------------------------------------ streaming filter
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 struct Raw {  // 8 logits as loaded: bf16 -> a only (4 dwords); fp32 (or element loads) -> a, b
     u32x4 a, b;
 };
 
-constexpr uint32_t kNegInfF32 = 0xFF800000u, kNegInfBf16x2 = 0xFF80FF80u;
+constexpr uint32_t kNegInfF32 = 0xFF800000u;
 
-// RAWF32: registers hold fp32 bit patterns (fp32 rows, or rows read element by element).
+// Tokens one lane loads per tile: 32 bytes per row when rows are read with 128-bit loads.
+template <int DT, bool VEC>
+struct TileShape {
+    static constexpr int kTokPerThread = (VEC && DT == ERSD_BF16) ? 16 : 8;
+    static constexpr int kTile = kThreads * kTokPerThread;
+};
+
 template <int DT, bool VEC>
 __device__ __forceinline__ Raw load_raw(const char* row, int32_t i0, int32_t end) {
     Raw r;
     if (VEC) {
-        if (i0 >= end) {
-            const uint32_t f = DT == ERSD_BF16 ? kNegInfBf16x2 : kNegInfF32;
-            r.a = u32x4{f, f, f, f};
-            r.b = r.a;
-        } else if (DT == ERSD_BF16) {
-            r.a = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + (size_t)i0 * 2));
-            r.b = r.a;
+        // Two unconditional 128-bit loads (no branch, so the compiler can count loads in flight exactly).  i0 and
+        // end are multiples of 8 and the segment is not empty; groups past the end re-read the segment's last
+        // group instead, and the refine step never accepts a token index >= end.
+        const int32_t last = end - kGroup;
+        if (DT == ERSD_BF16) {
+            const int32_t ia = i0 < last ? i0 : last;
+            const int32_t ib = i0 + kGroup < last ? i0 + kGroup : last;
+            r.a = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + (size_t)ia * 2));
+            r.b = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + (size_t)ib * 2));
         } else {
-            const u32x4* p = reinterpret_cast<const u32x4*>(row + (size_t)i0 * 4);
+            const int32_t ia = i0 < last ? i0 : last;
+            const u32x4* p = reinterpret_cast<const u32x4*>(row + (size_t)ia * 4);
             r.a = __builtin_nontemporal_load(p);
             r.b = __builtin_nontemporal_load(p + 1);
         }
-    } else {
+    } else {  // element loads; registers hold fp32 bit patterns
         uint32_t f[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -254,14 +283,14 @@ __device__ __forceinline__ void unpack(const Raw& r, float l[8]) {
     }
 }
 
-// Upper bound of -log2 e from the word x alone (see file header); slack below is added to tau instead.
+// Upper bound of -log2 e from the word x alone (see file header); slack is added to tau instead.
 __device__ __forceinline__ float gumbel2_upper(uint32_t x) {
     const float xf = (float)x;
     return fmaf((float)(int32_t)__float_as_uint(xf), -0x1p-23f, 159.0f);
 }
 
 // log2 of e = -ln(1 - v) in fp32.  |error| < 2^-7 given v_log_f32 within a few ulp (checked on device by
-// the test suite); callers use kRefineErr = 2^-5.
+// the library's self-test); callers use kRefineErr = 2^-5.
 __device__ __forceinline__ float log2_exponential(uint32_t x) {
     if (x < (1u << 23)) {  // v < 2^-9, exact in fp32: series of -ln(1-v)
         const float v = ((float)x + 0.5f) * 0x1p-32f;
@@ -277,6 +306,10 @@ __device__ __forceinline__ float log2_exponential(uint32_t x) {
 constexpr float kRefineErr = 0x1p-5f;
 constexpr float kRelErr = 0x1p-20f;
 constexpr float kUpperSlack = 0x1p-10f;
+constexpr float kTauInit = -3.0e38f;  // below every finite score; -inf scores never reach it
+
+// error bound of an fp32 score s2 (log2 units) against the true score
+__device__ __forceinline__ float refine_err(float s2) { return fmaf(fabsf(s2), kRelErr, kRefineErr); }
 
 __device__ __forceinline__ int32_t ordered_int(float f) {
     const int32_t i = __float_as_int(f);
@@ -293,55 +326,164 @@ __device__ __forceinline__ float wave_max(float v) {
     return v;
 }
 
-struct Lds {
-    int32_t tau[2];      // ordered-int encoding of the workgroup's lower bound, per side
-    int32_t count[2];    // candidates appended (may exceed kListCap: overflow)
-    int32_t list[2][kListCap];
-    double red_s[kThreads / kWave];
-    int32_t red_i[kThreads / kWave];
-};
+__device__ __forceinline__ float lds_tau(const Lds& lds, int side) {
+    return from_ordered_int(__hip_atomic_load(&lds.tau[side], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+}
 
 // One side's refine step for one token of one lane.
-__device__ __forceinline__ void refine_token(float logit, float l2e, float c2, int32_t idx, float& tau, Lds& lds,
-                                             int side) {
+__device__ __forceinline__ void refine_token(float logit, uint32_t x, float l2e, float c2, int32_t idx, float& tau,
+                                             Lds& lds, int side) {
     const float s2 = fmaf(logit, c2, -l2e);
-    const float err = fmaf(fabsf(s2), kRelErr, kRefineErr);
+    const float err = refine_err(s2);
     if (s2 > -INFINITY && s2 + err >= tau) {
         const int32_t pos = atomicAdd(&lds.count[side], 1);
-        if (pos < kListCap) lds.list[side][pos] = idx;
+        if (pos < kListCap) {
+            lds.idx[side][pos] = idx;
+            lds.word[side][pos] = x;
+            lds.logit[side][pos] = logit;
+        }
         tau = fmaxf(tau, s2 - err);
     }
 }
 
+// Element e (a run-time, wavefront-uniform index) of a lane's registers, by selects: keeps the rare refine loop
+// rolled up and the arrays in registers.
+__device__ __forceinline__ uint32_t pick4(const u32x4& v, int e) {
+    uint32_t r = v.x;
+    r = e == 1 ? v.y : r;
+    r = e == 2 ? v.z : r;
+    r = e == 3 ? v.w : r;
+    return r;
+}
+template <bool RAWF32>
+__device__ __forceinline__ float raw_logit(const Raw& r, int e) {
+    if (RAWF32) return __uint_as_float(e < 4 ? pick4(r.a, e) : pick4(r.b, e - 4));
+    const uint32_t w = pick4(r.a, e >> 1);
+    return __uint_as_float((e & 1) ? (w & 0xffff0000u) : (w << 16));
+}
+
+// the same with a compile-time index: a plain register reference
+template <bool RAWF32>
+__device__ __forceinline__ float raw_logit_const(const Raw& r, int e) {
+    if (RAWF32) return __uint_as_float(e < 4 ? r.a[e & 3] : r.b[e & 3]);
+    const uint32_t w = r.a[(e >> 1) & 3];
+    return __uint_as_float((e & 1) ? (w & 0xffff0000u) : (w << 16));
+}
+
+// The rare second look at a lane's 8 tokens: those whose upper bound reaches tau get an fp32 score with an error
+// margin; what can still be the maximum goes to the candidate list and raises tau (lane, wavefront, workgroup).
+template <bool RAWF32, bool HASQ>
+__device__ __forceinline__ void refine_tile(Lds& lds, float c2, int32_t i0, int32_t end, const Raw& rq, const Raw& rp,
+                                            const uint32_t (&x)[8], bool flag, float tauq_m, float taup_m,
+                                            float& tauq, float& taup) {
+    if (!flag) return;
+    // which of this lane's (token, side) bounds reach tau: bits 0-7 target side, 8-15 draft side
+    uint32_t mask = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float t = gumbel2_upper(x[e]);
+        if (fmaf(raw_logit_const<RAWF32>(rp, e), c2, t) >= taup_m) mask |= 1u << e;
+        if (HASQ && fmaf(raw_logit_const<RAWF32>(rq, e), c2, t) >= tauq_m) mask |= 1u << (8 + e);
+    }
+    const float taup0 = taup, tauq0 = tauq;
+    while (mask) {  // usually a single bit in a single lane
+        const int b = __builtin_ctz(mask);
+        mask &= mask - 1;
+        const int e = b & 7;
+        const bool isq = HASQ && b >= 8;
+        const int32_t idx = i0 + e;
+        if (idx < end) {
+            const uint32_t xe = e < 4 ? pick4(u32x4{x[0], x[1], x[2], x[3]}, e) : pick4(u32x4{x[4], x[5], x[6], x[7]}, e - 4);
+            const float lq = HASQ ? raw_logit<RAWF32>(rq, e) : 0.0f;
+            const float lp = raw_logit<RAWF32>(rp, e);
+            float tau = isq ? tauq : taup;
+            refine_token(isq ? lq : lp, xe, log2_exponential(xe), c2, idx, tau, lds, isq ? 0 : 1);
+            if (isq) tauq = tau;
+            else taup = tau;
+        }
+    }
+    // publish what this lane learned; the other lanes merge it in at their next tile
+    if (taup > taup0) atomicMax(&lds.tau[1], ordered_int(taup));
+    if (HASQ && tauq > tauq0) atomicMax(&lds.tau[0], ordered_int(tauq));
+}
+
+// The per-iteration work of one lane: 8 tokens of one or two rows.
+template <bool RAWF32, bool HASQ>
+__device__ __forceinline__ void filter_tile(const RaceArgs& a, const Seg& c, Lds& lds, int32_t i0, const Raw& rq,
+                                            const Raw& rp, float& tauq, float& taup) {
+    const float c2 = a.c2;
+    // the workgroup's bound, possibly raised by another wavefront since the last iteration
+    taup = fmaxf(taup, lds_tau(lds, 1));
+    if (HASQ) tauq = fmaxf(tauq, lds_tau(lds, 0));
+    const float taup_m = with_margin(taup);
+    const float tauq_m = HASQ ? with_margin(tauq) : 0.0f;
+
+    uint32_t x[8];
+    philox4x32_10((uint32_t)i0 >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, x);
+    philox4x32_10(((uint32_t)i0 >> 2) + 1, c.c1, c.c2, c.c3, a.key0, a.key1, x + 4);
+    float lp[8], lq[8];
+    unpack<RAWF32>(rp, lp);
+    if (HASQ) unpack<RAWF32>(rq, lq);
+
+    float accp = -INFINITY, accq = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float t = gumbel2_upper(x[e]);
+        accp = fmaxf(accp, fmaf(lp[e], c2, t));
+        if (HASQ) accq = fmaxf(accq, fmaf(lq[e], c2, t));
+    }
+    bool flag = accp >= taup_m;
+    if (HASQ) flag = flag || (accq >= tauq_m);
+
+    if (__builtin_amdgcn_ballot_w64(flag) != 0)  // rare: some lane holds a token that may matter
+        refine_tile<RAWF32, HASQ>(lds, c2, i0, c.end, rq, rp, x, flag, tauq_m, taup_m, tauq, taup);
+}
+
+// One lane's share of a tile: 8 tokens, or 16 as two groups of 8 when the registers hold bf16.
 template <int DT, bool VEC, bool HASQ>
-__device__ void race_filtered_body(const RaceArgs& a, const RowCtx& c, Lds& lds) {
+__device__ __forceinline__ void filter_lane(const RaceArgs& a, const Seg& c, Lds& lds, int32_t i0, const Raw& rq,
+                                            const Raw& rp, float& tauq, float& taup) {
     constexpr bool RAWF32 = (DT == ERSD_F32) || !VEC;
+    if (TileShape<DT, VEC>::kTokPerThread == 16) {
+        Raw hq, hp;
+        hq.a = rq.a; hq.b = rq.a; hp.a = rp.a; hp.b = rp.a;
+        filter_tile<RAWF32, HASQ>(a, c, lds, i0, hq, hp, tauq, taup);
+        hq.a = rq.b; hq.b = rq.b; hp.a = rp.b; hp.b = rp.b;
+        filter_tile<RAWF32, HASQ>(a, c, lds, i0 + kGroup, hq, hp, tauq, taup);
+    } else {
+        filter_tile<RAWF32, HASQ>(a, c, lds, i0, rq, rp, tauq, taup);
+    }
+}
+
+template <int DT, bool VEC, bool HASQ>
+__device__ void filter_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
+    constexpr bool RAWF32 = (DT == ERSD_F32) || !VEC;
+    constexpr int kTokPerThread = TileShape<DT, VEC>::kTokPerThread;
+    constexpr int kTile = TileShape<DT, VEC>::kTile;
     const int tid = threadIdx.x;
     const float c2 = a.c2;
 
-    if (tid < 2) {
-        lds.tau[tid] = ordered_int(-3.0e38f);
-        lds.count[tid] = 0;
-    }
-    __syncthreads();
+    // first tile's loads go out before anything else; the bootstrap below reads them
+    Raw qa, pa, qb, pb;
+    const int32_t first = c.begin + tid * kTokPerThread;
+    pa = load_raw<DT, VEC>(c.prow, first, c.end);
+    if (HASQ) qa = load_raw<DT, VEC>(c.qrow, first, c.end);
 
-    // Bootstrap: a lower bound of the maximum from the first two tokens of every lane's first group.
-    float tauq = -3.0e38f, taup = -3.0e38f;
+    // Bootstrap: each wavefront starts from a lower bound of the maximum taken from the first two tokens of every
+    // lane's first group (no barrier: the workgroup's bound in LDS is merged in at every tile).
+    float tauq = kTauInit, taup = kTauInit;
     {
-        const int32_t i0 = c.begin + tid * kTokPerThread;
-        if (i0 < c.end) {
-            uint32_t w[4];
-            philox4x32_10((uint32_t)i0 >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, w);
+        uint32_t w[4];
+        philox4x32_10((uint32_t)first >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, w);
 #pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                if (i0 + e < c.end) {
-                    const float l2e = log2_exponential(w[e]);
-                    const float sp = fmaf(widen_elem(c.prow, DT, i0 + e), c2, -l2e);
-                    if (sp > -INFINITY) taup = fmaxf(taup, sp - fmaf(fabsf(sp), kRelErr, kRefineErr));
-                    if (HASQ) {
-                        const float sq = fmaf(widen_elem(c.qrow, DT, i0 + e), c2, -l2e);
-                        if (sq > -INFINITY) tauq = fmaxf(tauq, sq - fmaf(fabsf(sq), kRelErr, kRefineErr));
-                    }
+        for (int e = 0; e < 2; ++e) {
+            if (first + e < c.end) {
+                const float l2e = log2_exponential(w[e]);
+                const float sp = fmaf(raw_logit<RAWF32>(pa, e), c2, -l2e);
+                if (sp > -INFINITY) taup = fmaxf(taup, sp - refine_err(sp));
+                if (HASQ) {
+                    const float sq = fmaf(raw_logit<RAWF32>(qa, e), c2, -l2e);
+                    if (sq > -INFINITY) tauq = fmaxf(tauq, sq - refine_err(sq));
                 }
             }
         }
@@ -351,113 +493,167 @@ __device__ void race_filtered_body(const RaceArgs& a, const RowCtx& c, Lds& lds)
             atomicMax(&lds.tau[1], ordered_int(taup));
             if (HASQ) atomicMax(&lds.tau[0], ordered_int(tauq));
         }
-        __syncthreads();
-        taup = from_ordered_int(lds.tau[1]);
-        if (HASQ) tauq = from_ordered_int(lds.tau[0]);
     }
 
-    Raw rq, rp;
-    {
-        const int32_t i0 = c.begin + tid * kTokPerThread;
-        rp = load_raw<DT, VEC>(c.prow, i0, c.end);
-        if (HASQ) rq = load_raw<DT, VEC>(c.qrow, i0, c.end);
-    }
-    for (int32_t base = c.begin; base < c.end; base += kTokPerIter) {
+    // two tiles per trip, registers ping-pong so that a tile's loads have a whole tile of work to arrive
+    for (int32_t base = c.begin; base < c.end; base += 2 * kTile) {
         const int32_t i0 = base + tid * kTokPerThread;
-        Raw nq, np;
-        {
-            const int32_t n0 = i0 + kTokPerIter;
-            np = load_raw<DT, VEC>(c.prow, n0, c.end);
-            if (HASQ) nq = load_raw<DT, VEC>(c.qrow, n0, c.end);
-        }
-        // the workgroup's bound, possibly raised by another wavefront since the last iteration
-        taup = fmaxf(taup, from_ordered_int(__hip_atomic_load(&lds.tau[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)));
-        if (HASQ)
-            tauq = fmaxf(tauq, from_ordered_int(__hip_atomic_load(&lds.tau[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)));
-        const float taup_m = with_margin(taup);
-        const float tauq_m = HASQ ? with_margin(tauq) : 0.0f;
+        pb = load_raw<DT, VEC>(c.prow, i0 + kTile, c.end);
+        if (HASQ) qb = load_raw<DT, VEC>(c.qrow, i0 + kTile, c.end);
+        filter_lane<DT, VEC, HASQ>(a, c, lds, i0, qa, pa, tauq, taup);
+        if (base + kTile >= c.end) break;
+        pa = load_raw<DT, VEC>(c.prow, i0 + 2 * kTile, c.end);
+        if (HASQ) qa = load_raw<DT, VEC>(c.qrow, i0 + 2 * kTile, c.end);
+        filter_lane<DT, VEC, HASQ>(a, c, lds, i0 + kTile, qb, pb, tauq, taup);
+    }
+}
 
-        uint32_t x[8];
-        philox4x32_10((uint32_t)i0 >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, x);
-        philox4x32_10(((uint32_t)i0 >> 2) + 1, c.c1, c.c2, c.c3, a.key0, a.key1, x + 4);
-        float lp[8], lq[8];
-        unpack<RAWF32>(rp, lp);
-        if (HASQ) unpack<RAWF32>(rq, lq);
+// fp32 score of a (logit, word) record, exactly as the refine step computes it
+__device__ __forceinline__ float score2(float logit, uint32_t word, float c2) {
+    return fmaf(logit, c2, -log2_exponential(word));
+}
 
-        float accp = -INFINITY, accq = -INFINITY;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float t = gumbel2_upper(x[e]);
-            accp = fmaxf(accp, fmaf(lp[e], c2, t));
-            if (HASQ) accq = fmaxf(accq, fmaf(lq[e], c2, t));
-        }
-        bool flag = accp >= taup_m;
-        if (HASQ) flag = flag || (accq >= tauq_m);
-
-        if (__builtin_amdgcn_ballot_w64(flag) != 0) {  // rare: some lane holds a token that may matter
-            if (flag) {
-#pragma unroll 1
-                for (int e = 0; e < 8; ++e) {
-                    const int32_t idx = i0 + e;
-                    const float t = gumbel2_upper(x[e]);
-                    const bool fp = fmaf(lp[e], c2, t) >= taup_m;
-                    const bool fq = HASQ && (fmaf(lq[e], c2, t) >= tauq_m);
-                    if ((fp || fq) && idx < c.end) {
-                        const float l2e = log2_exponential(x[e]);
-                        if (fp) refine_token(lp[e], l2e, c2, idx, taup, lds, 1);
-                        if (fq) refine_token(lq[e], l2e, c2, idx, tauq, lds, 0);
-                    }
-                }
-            }
-            taup = wave_max(taup);
-            if (HASQ) tauq = wave_max(tauq);
-            if ((tid & (kWave - 1)) == 0) {
-                atomicMax(&lds.tau[1], ordered_int(taup));
-                if (HASQ) atomicMax(&lds.tau[0], ordered_int(tauq));
-            }
-        }
-        rp = np;
-        if (HASQ) rq = nq;
+// A whole segment: stream, then hand the survivors of each side to the finishing kernel.
+template <int DT, bool VEC>
+__device__ void race_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
+    const int tid = threadIdx.x;
+    if (tid < 2) {
+        lds.tau[tid] = ordered_int(kTauInit);
+        lds.count[tid] = 0;
+        lds.nsurv[tid] = 0;
+    }
+    __syncthreads();
+    if (!a.exhaustive) {
+        if (c.qrow) filter_segment<DT, VEC, true>(a, c, lds);
+        else filter_segment<DT, VEC, false>(a, c, lds);
     }
     __syncthreads();
 
-    // Exact stage: fp64 scores of the candidates, (score, lowest index) reduction, one partial per side.
-#pragma unroll 1
-    for (int side = HASQ ? 0 : 1; side < 2; ++side) {
-        const char* row = side == 0 ? c.qrow : c.prow;
-        const int32_t n = lds.count[side];
-        if (n > kListCap) {  // workgroup-uniform: candidate list overflowed, score the whole split exactly
-            exhaustive_side<DT>(a, c, row, side, lds.red_s, lds.red_i);
-            continue;
+    // Wavefronts 0-1 take the draft side, 2-3 the target side.
+    const int side = tid / (kThreads / 2);
+    const int half_tid = tid % (kThreads / 2);
+    const char* row = side == 0 ? c.qrow : c.prow;
+    const int32_t n = row ? lds.count[side] : 0;
+    const bool listed = row && !a.exhaustive && n <= kListCap;
+    if (listed) {  // keep the candidates whose interval still reaches the final lower bound
+        const float tau = lds_tau(lds, side);
+        for (int32_t t = half_tid; t < n; t += kThreads / 2) {
+            const float s2 = score2(lds.logit[side][t], lds.word[side][t], a.c2);
+            if (s2 + refine_err(s2) >= tau) {
+                const int32_t k = atomicAdd(&lds.nsurv[side], 1);
+                if (k < kMaxSurvivors) lds.surv[side][k] = t;
+            }
         }
-        double bs = -INFINITY;
-        int32_t bi = -1;
-        for (int32_t t = tid; t < n; t += kThreads) {
-            const int32_t i = lds.list[side][t];
-            const double s = exact_score_at(row, DT, i, a, c.c1, c.c2, c.c3);
-            if (bi < 0 || better(s, i, bs, bi)) { bs = s; bi = i; }
+    }
+    __syncthreads();
+    SegOut* out = row ? a.out + (c.row * 2 + side) * a.part.nslot + c.slot : nullptr;
+    const int32_t ns = lds.nsurv[side];
+    const bool common = listed && ns <= kMaxSurvivors;
+    double bs = -INFINITY;
+    int32_t bi = -1;
+    if (common) {  // 0 (no finite score), 1 or a few survivors
+        if (half_tid == 0) out->count = ns;
+        if (half_tid < ns) {
+            const int32_t t = lds.surv[side][half_tid];
+            Cand k;
+            k.idx = lds.idx[side][t];
+            k.word = lds.word[side][t];
+            k.logit = lds.logit[side][t];
+            k.s2 = score2(k.logit, k.word, a.c2);
+            out->c[half_tid] = k;
         }
-        block_argmax(bs, bi, lds.red_s, lds.red_i);
-        if (tid == 0) {
-            if (bi < 0) { bs = -INFINITY; bi = c.begin; }  // no finite score in this split
-            store_partial(a, c, side, bs, bi);
+    } else if (row) {
+        // Rare: too many survivors, an overflowed candidate list, or the reference mode.  Score in fp64 here and
+        // hand on the single exact winner.
+        if (a.exhaustive || n > kListCap) {
+            exhaustive_half<DT>(a, c, row, half_tid, bs, bi);
+        } else {
+            for (int32_t t = half_tid; t < n; t += kThreads / 2) {
+                const int32_t i = lds.idx[side][t];
+                const double s = exact_score(lds.logit[side][t], a.T, lds.word[side][t]);
+                if (bi < 0 || better(s, i, bs, bi)) { bs = s; bi = i; }
+            }
+        }
+        wave_argmax(bs, bi);
+        if ((tid & (kWave - 1)) == 0) { lds.red_s[tid / kWave] = bs; lds.red_i[tid / kWave] = bi; }
+    }
+    __syncthreads();
+    if (!common && row && half_tid == 0) {
+        const int w0 = side * 2;
+        bs = lds.red_s[w0];
+        bi = lds.red_i[w0];
+        const double os = lds.red_s[w0 + 1];
+        const int32_t oi = lds.red_i[w0 + 1];
+        if (oi >= 0 && (bi < 0 || better(os, oi, bs, bi))) { bs = os; bi = oi; }
+        if (bi < 0 || !(bs > -INFINITY)) {
+            out->count = 0;
+        } else {
+            uint32_t w[4];
+            philox4x32_10((uint32_t)bi >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, w);
+            Cand k;
+            k.idx = bi;
+            k.word = w[bi & 3];
+            k.logit = widen_elem(row, DT, bi);
+            k.s2 = score2(k.logit, k.word, a.c2);
+            out->count = 1;
+            out->c[0] = k;
         }
     }
 }
 
+#ifndef ERSD_WAVES_PER_EU
+#define ERSD_WAVES_PER_EU 4
+#endif
+
 template <int DT, bool VEC>
-__global__ void __launch_bounds__(kThreads) race_filtered_kernel(RaceArgs a) {
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ERSD_WAVES_PER_EU, 8)))
+race_kernel(RaceArgs a) {
     __shared__ Lds lds;
-    const RowCtx c = make_ctx<DT>(a);
-    if (c.qrow) race_filtered_body<DT, VEC, true>(a, c, lds);
-    else race_filtered_body<DT, VEC, false>(a, c, lds);
+    const Part& p = a.part;
+    uint64_t pos = part_start_pos(p, blockIdx.x);
+    const uint64_t pos_end = part_start_pos(p, blockIdx.x + 1);
+    const size_t es = DT == ERSD_F32 ? 4 : 2;
+    if (pos >= pos_end) return;
+    // (row, sequence, position, prompt, draft) of the first segment; later segments start at the next row's
+    // first group, so they follow by counting up
+    uint64_t row = pos / p.V8;
+    uint32_t g0 = (uint32_t)(pos - row * p.V8);
+    uint64_t seq = row / p.kt;
+    uint32_t j = (uint32_t)(row - seq * p.kt);
+    uint32_t prompt = (uint32_t)(seq / a.m), d = (uint32_t)(seq - (uint64_t)prompt * a.m);
+    while (pos < pos_end) {  // one row segment per trip (workgroup-uniform)
+        Seg c;
+        c.row = row;
+        const uint64_t left = pos_end - pos;
+        const uint32_t g1 = left < (uint64_t)(p.V8 - g0) ? g0 + (uint32_t)left : p.V8;
+        c.prow = a.target + (size_t)row * (size_t)a.V * es;
+        c.qrow = j < p.kd ? a.draft + (size_t)(seq * p.kd + j) * (size_t)a.V * es : nullptr;
+        c.c1 = j;
+        c.c2 = prompt;
+        c.c3 = d;
+        c.begin = (int32_t)(g0 * 8);
+        const int64_t e = (int64_t)g1 * 8;
+        c.end = e < a.V ? (int32_t)e : a.V;
+        // a segment that starts at its row's first group is that row's first writer
+        c.slot = g0 == 0 ? 0 : blockIdx.x - part_first_block(p, row);
+        race_segment<DT, VEC>(a, c, lds);
+        pos += g1 - g0;
+        g0 = 0;
+        ++row;
+        if (++j == p.kt) {
+            j = 0;
+            ++seq;
+            if (++d == (uint32_t)a.m) { d = 0; ++prompt; }
+        }
+    }
 }
 
 // ------------------------------------------------------------------------------------------ finishing kernel
 struct FinishArgs {
-    const Partial* partials;
-    int32_t nsplit;
-    int32_t kd, kt, m;
+    const SegOut* out;
+    double T;
+    Part part;
+    int32_t m;
     int32_t variant;
     const int32_t* parent;
     int32_t* draft_tokens;
@@ -468,34 +664,96 @@ struct FinishArgs {
     int32_t* accept_node;
 };
 
-__device__ __forceinline__ int32_t combine_partials(const Partial* p, int32_t nsplit) {
-    double bs = p[0].score;
-    int32_t bi = p[0].idx;
-    for (int32_t s = 1; s < nsplit; ++s)
-        if (p[s].score > bs) { bs = p[s].score; bi = p[s].idx; }  // splits are in index order: ties keep the lower
-    return bi;
+// The winner of one row side from the survivors its segments left: decided by the fp32 intervals when one lies
+// above all others, by fp64 scores (lowest index on ties) among the contenders otherwise.  Eight adjacent lanes
+// work on one row side, each taking every eighth segment slot; every lane of the wavefront must call this
+// (`active` false for lanes without work) because the lanes of a group meet in shuffles.
+__device__ int32_t resolve_row(const SegOut* o, uint32_t nslots, double T, bool active, int lane8) {
+    float lstar = -INFINITY;
+    int32_t total = 0;
+    if (active)
+        for (uint32_t s = lane8; s < nslots; s += 8) {
+            const SegOut so = o[s];
+#pragma unroll
+            for (int32_t k = 0; k < kMaxSurvivors; ++k)
+                if (k < so.count) {
+                    lstar = fmaxf(lstar, so.c[k].s2 - refine_err(so.c[k].s2));
+                    ++total;
+                }
+        }
+#pragma unroll
+    for (int off = 4; off > 0; off >>= 1) {
+        lstar = fmaxf(lstar, __shfl_xor(lstar, off, 8));
+        total += __shfl_xor(total, off, 8);
+    }
+    int32_t contenders = 0, only = -1;
+    if (active && total > 0)
+        for (uint32_t s = lane8; s < nslots; s += 8) {
+            const SegOut so = o[s];
+#pragma unroll
+            for (int32_t k = 0; k < kMaxSurvivors; ++k)
+                if (k < so.count && so.c[k].s2 + refine_err(so.c[k].s2) >= lstar) {
+                    ++contenders;
+                    only = so.c[k].idx;
+                }
+        }
+#pragma unroll
+    for (int off = 4; off > 0; off >>= 1) {
+        contenders += __shfl_xor(contenders, off, 8);
+        only = max(only, __shfl_xor(only, off, 8));
+    }
+    if (total == 0) return 0;  // every score of the row is -inf: lowest index
+    double bs = -INFINITY;
+    int32_t bi = -1;
+    if (contenders > 1 && active)  // fp32 cannot tell: score the contenders exactly
+        for (uint32_t s = lane8; s < nslots; s += 8) {
+            const SegOut so = o[s];
+            for (int32_t k = 0; k < so.count; ++k) {
+                const Cand cd = so.c[k];
+                if (cd.s2 + refine_err(cd.s2) >= lstar) {
+                    const double sc = exact_score(cd.logit, T, cd.word);
+                    if (bi < 0 || better(sc, cd.idx, bs, bi)) { bs = sc; bi = cd.idx; }
+                }
+            }
+        }
+#pragma unroll
+    for (int off = 4; off > 0; off >>= 1) {
+        const double os = __shfl_xor(bs, off, 8);
+        const int32_t oi = __shfl_xor(bi, off, 8);
+        if (oi >= 0 && (bi < 0 || better(os, oi, bs, bi))) { bs = os; bi = oi; }
+    }
+    return contenders > 1 ? bi : only;
 }
 
-// One workgroup per prompt b: tokens of all its rows, then accept lengths.
-__global__ void __launch_bounds__(kThreads) finish_kernel(FinishArgs f) {
-    const int32_t b = blockIdx.x;
+// Tokens: every (row, side) pair is resolved by eight lanes; 32 pairs per workgroup.
+__global__ void __launch_bounds__(kThreads) resolve_kernel(FinishArgs f) {
     const int tid = threadIdx.x;
-    const int64_t seq0 = (int64_t)b * f.m;
-    const int32_t nrows = f.m * f.kt;  // target rows of this prompt
-    for (int32_t t = tid; t < nrows * 2; t += kThreads) {
-        const int32_t side = t & 1, r = t >> 1;
-        const int32_t d = r / f.kt, j = r % f.kt;
-        const int64_t row = (seq0 + d) * f.kt + j;
-        if (side == 0 && j >= f.kd) continue;
-        const int32_t tok = combine_partials(f.partials + ((size_t)row * 2 + side) * f.nsplit, f.nsplit);
-        if (side == 0) f.draft_tokens[(seq0 + d) * f.kd + j] = tok;
-        else f.target_tokens[row] = tok;
+    const Part& p = f.part;
+    const uint64_t item = (uint64_t)blockIdx.x * (kThreads / 8) + (tid >> 3);
+    const uint64_t row = item >> 1;
+    const int side = (int)(item & 1);
+    const uint32_t j = (uint32_t)(row % p.kt);
+    const bool active = row < p.rows && (side == 1 || j < p.kd);
+    const uint64_t r = active ? row : 0;
+    const uint32_t n = active ? part_last_block(p, r) - part_first_block(p, r) + 1 : 0;
+    const int32_t tok = resolve_row(f.out + (r * 2 + side) * p.nslot, n, f.T, active, tid & 7);
+    if (active && (tid & 7) == 0) {
+        if (side == 1) f.target_tokens[r] = tok;
+        else f.draft_tokens[(r / p.kt) * p.kd + j] = tok;
     }
-    __syncthreads();  // tokens of this prompt were written by this workgroup and are re-read below
+}
+
+// Accept lengths of prompt b from its tokens (first disagreement per draft, best draft, or the tree walk).
+// Called by a whole workgroup after the prompt's tokens are visible to it.
+__device__ void accept_prompt(const FinishArgs& f, int32_t b) {
+    const int tid = threadIdx.x;
+    const Part& p = f.part;
+    const int32_t kt = (int32_t)p.kt, kd = (int32_t)p.kd;
+    const int64_t seq0 = (int64_t)b * f.m;
 
     if (f.variant == ERSD_VARIANT_TREE) {
         // agree-path depth of every node by walking its ancestors (bounded by the node index)
-        const int32_t N = f.kt;
+        const int32_t N = kt;
         const int32_t* dt = f.draft_tokens + (int64_t)b * N;
         const int32_t* tt = f.target_tokens + (int64_t)b * N;
         int32_t best_depth = 0, best_node = -1;
@@ -505,10 +763,10 @@ __global__ void __launch_bounds__(kThreads) finish_kernel(FinishArgs f) {
             while (true) {
                 if (dt[cur] != tt[cur]) { ok = false; break; }
                 ++depth;
-                const int32_t p = f.parent[cur];
-                if (p == -1) break;
-                if (p < 0 || p >= cur) { ok = false; break; }  // malformed entry; p < cur bounds the walk
-                cur = p;
+                const int32_t pa = f.parent[cur];
+                if (pa == -1) break;
+                if (pa < 0 || pa >= cur) { ok = false; break; }  // malformed entry; pa < cur bounds the walk
+                cur = pa;
             }
             if (ok && depth > best_depth) { best_depth = depth; best_node = n; }  // increasing n per thread
         }
@@ -520,11 +778,11 @@ __global__ void __launch_bounds__(kThreads) finish_kernel(FinishArgs f) {
                 best_node = on;
             }
         }
-        __shared__ int32_t wd[kThreads / kWave], wn[kThreads / kWave];
+        __shared__ int32_t wd[kWaves], wn[kWaves];
         if ((tid & (kWave - 1)) == 0) { wd[tid / kWave] = best_depth; wn[tid / kWave] = best_node; }
         __syncthreads();
         if (tid == 0) {
-            for (int w = 1; w < kThreads / kWave; ++w)
+            for (int w = 1; w < kWaves; ++w)
                 if (wd[w] > best_depth || (wd[w] == best_depth && wn[w] >= 0 && (best_node < 0 || wn[w] < best_node))) {
                     best_depth = wd[w];
                     best_node = wn[w];
@@ -537,10 +795,10 @@ __global__ void __launch_bounds__(kThreads) finish_kernel(FinishArgs f) {
 
     // sequence / multi: first mismatch per draft
     for (int32_t d = tid; d < f.m; d += kThreads) {
-        const int32_t* dt = f.draft_tokens + (seq0 + d) * f.kd;
-        const int32_t* tt = f.target_tokens + (seq0 + d) * f.kt;
+        const int32_t* dt = f.draft_tokens + (seq0 + d) * kd;
+        const int32_t* tt = f.target_tokens + (seq0 + d) * kt;
         int32_t acc = 0;
-        while (acc < f.kd && dt[acc] == tt[acc]) ++acc;
+        while (acc < kd && dt[acc] == tt[acc]) ++acc;
         f.accept_len[seq0 + d] = acc;
     }
     if (f.best_len) {
@@ -555,6 +813,34 @@ __global__ void __launch_bounds__(kThreads) finish_kernel(FinishArgs f) {
             f.best_draft[b] = bd;
         }
     }
+}
+
+// Accept lengths: one workgroup per prompt b, reading the tokens the previous kernel wrote.
+__global__ void __launch_bounds__(kThreads) accept_kernel(FinishArgs f) { accept_prompt(f, blockIdx.x); }
+
+// Both steps in one launch, for prompts with few rows: workgroup b resolves the rows of prompt b itself.
+__global__ void __launch_bounds__(kThreads) finish_kernel(FinishArgs f) {
+    const int32_t b = blockIdx.x;
+    const int tid = threadIdx.x;
+    const Part& p = f.part;
+    const uint64_t row0 = (uint64_t)b * f.m * p.kt;
+    const uint32_t nitems = (uint32_t)f.m * p.kt * 2;
+    for (uint32_t first = 0; first < nitems; first += kThreads / 8) {  // uniform trip count: lanes meet in shuffles
+        const uint32_t item = first + (tid >> 3);
+        const uint64_t row = row0 + (item >> 1);
+        const int side = (int)(item & 1);
+        const uint32_t j = (uint32_t)(row % p.kt);
+        const bool active = item < nitems && (side == 1 || j < p.kd);
+        const uint64_t r = active ? row : row0;
+        const uint32_t n = active ? part_last_block(p, r) - part_first_block(p, r) + 1 : 0;
+        const int32_t tok = resolve_row(f.out + (r * 2 + side) * p.nslot, n, f.T, active, tid & 7);
+        if (active && (tid & 7) == 0) {
+            if (side == 1) f.target_tokens[r] = tok;
+            else f.draft_tokens[(r / p.kt) * p.kd + j] = tok;
+        }
+    }
+    __syncthreads();  // this prompt's tokens were written by this workgroup and are re-read below
+    accept_prompt(f, b);
 }
 
 // ------------------------------------------------------------------------------------------ self-check
@@ -586,10 +872,8 @@ __global__ void zero_counters_kernel(unsigned long long* counters) {
 }
 
 // ------------------------------------------------------------------------------------------ host side
-struct Plan {
-    int32_t nsplit;
-    int32_t chunk;
-    int64_t rows;  // target rows = races
+struct Geometry {
+    int32_t B, m, kd, kt, V;
 };
 
 int env_int(const char* name, int dflt) {
@@ -598,46 +882,16 @@ int env_int(const char* name, int dflt) {
     return std::atoi(s);
 }
 
-// Split the vocabulary so that the grid has a few workgroups per SIMD even for few rows.
-Plan make_plan(int64_t rows, int32_t V) {
-    Plan p;
-    p.rows = rows;
-    const int64_t want_blocks = 256 * 8;  // 256 compute units
-    int64_t ns = (want_blocks + rows - 1) / rows;
-    const int64_t max_by_size = (V + 4 * kTokPerIter - 1) / (4 * kTokPerIter);  // at least 4 iterations per split
-    if (ns > max_by_size) ns = max_by_size;
-    const int forced = env_int("ERSD_FORCE_SPLIT", 0);  // tests only
-    if (forced > 0) ns = forced;
-    if (ns > kMaxSplit) ns = kMaxSplit;
-    if (ns < 1) ns = 1;
-    int64_t chunk = ((int64_t)V + ns - 1) / ns;
-    chunk = (chunk + kTokPerIter - 1) / kTokPerIter * kTokPerIter;
-    p.chunk = (int32_t)(chunk > 0x7fff0000LL ? 0x7fff0000LL : chunk);
-    p.nsplit = (int32_t)(((int64_t)V + p.chunk - 1) / p.chunk);
-    return p;
-}
-
 bool sizes_ok(int32_t B, int32_t m, int32_t kd, int32_t kt, int32_t V) {
     if (B < 1 || m < 1 || kd < 1 || kt < 1 || V < 1) return false;
-    if (V > 0x7fff0000) return false;                       // token indices and split ends stay in int32
+    if (V > 0x7fff0000) return false;                         // token indices stay in int32
     const int64_t rows = (int64_t)B * m * kt;
-    if (rows > (int64_t)0x7fffffff / kMaxSplit) return false;  // grid size and row counters stay in int32
+    if (rows > 0x7fffffff) return false;                      // grids and row indices
+    const int64_t v8 = ((int64_t)V + 7) / 8;
+    if (rows > ((int64_t)1 << 46) / v8) return false;         // cost units times workgroups stay below 2^63
+    if ((int64_t)B * m > 0x7fffffff) return false;            // sequence counters are 32-bit counter words
     return true;
 }
-
-int check_common(const void* dl, const void* tl, ersd_dtype dt, float T, const void* ws) {
-    if (!dl || !tl) return ERSD_ERR_NULL_POINTER;
-    if (dt != ERSD_F32 && dt != ERSD_BF16) return ERSD_ERR_UNSUPPORTED_DTYPE;
-    if (!(T > 0.0f) || !std::isfinite(T)) return ERSD_ERR_INVALID_ARG;
-    if (((uintptr_t)dl & 15) || ((uintptr_t)tl & 15) || ((uintptr_t)ws & 15)) return ERSD_ERR_MISALIGNED;
-    return ERSD_OK;
-}
-
-size_t workspace_for(const Plan& p) { return (size_t)p.rows * 2 * (size_t)p.nsplit * sizeof(Partial); }
-
-struct Geometry {
-    int32_t B, m, kd, kt, V;
-};
 
 // variant + public sizes -> rows per sequence; false if the sizes are not acceptable
 bool geometry(int variant, int32_t B, int32_t m, int32_t k_or_N, int32_t V, Geometry& g) {
@@ -651,54 +905,113 @@ bool geometry(int variant, int32_t B, int32_t m, int32_t k_or_N, int32_t V, Geom
     return sizes_ok(g.B, g.m, g.kd, g.kt, g.V);
 }
 
+// Partition for `blocks` resident workgroups (fewer if the job is small).
+Part make_part(const Geometry& g, uint32_t blocks) {
+    Part p;
+    p.V8 = (uint32_t)(((int64_t)g.V + 7) / 8);
+    p.kd = (uint32_t)g.kd;
+    p.kt = (uint32_t)g.kt;
+    p.rows = (uint64_t)g.B * g.m * g.kt;
+    p.pair_units = (uint64_t)kWPair * p.kd * p.V8;
+    p.Us = p.pair_units + (uint64_t)kWSingle * (p.kt - p.kd) * p.V8;
+    p.U = p.Us * (uint64_t)g.B * g.m;
+    uint64_t G = blocks;
+    const uint64_t by_quota = p.U / kMinQuota;
+    if (G > by_quota) G = by_quota;
+    if (G < 1) G = 1;
+    p.G = (uint32_t)G;
+    p.nslot = (uint32_t)((uint64_t)kWPair * p.V8 * p.G / p.U) + 2;
+    return p;
+}
+
+size_t workspace_for(const Geometry& g) {
+    const Part p = make_part(g, kMaxBlocks);  // slots per row grow with the workgroup count: size for the most
+    return (size_t)p.rows * 2 * p.nslot * sizeof(SegOut);
+}
+
+int check_common(const void* dl, const void* tl, ersd_dtype dt, float T, const void* ws) {
+    if (!dl || !tl) return ERSD_ERR_NULL_POINTER;
+    if (dt != ERSD_F32 && dt != ERSD_BF16) return ERSD_ERR_UNSUPPORTED_DTYPE;
+    if (!(T > 0.0f) || !std::isfinite(T)) return ERSD_ERR_INVALID_ARG;
+    if (((uintptr_t)dl & 15) || ((uintptr_t)tl & 15) || ((uintptr_t)ws & 15)) return ERSD_ERR_MISALIGNED;
+    return ERSD_OK;
+}
+
+template <typename K>
+int resident_blocks(K kernel, std::atomic<int>& cache) {
+    int v = cache.load(std::memory_order_relaxed);
+    if (v > 0) return v;
+    int per_cu = 0, dev = 0;
+    hipDeviceProp_t prop;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kThreads, 0) != hipSuccess || per_cu < 1 ||
+        hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
+        return -1;
+    v = per_cu * prop.multiProcessorCount;
+    if (v > (int)kMaxBlocks) v = (int)kMaxBlocks;
+    cache.store(v, std::memory_order_relaxed);
+    return v;
+}
+
+// Workgroups the race kernel is launched with: as many as are resident at once on the current device.
+int race_blocks(ersd_dtype dt, bool vec) {
+    static std::atomic<int> cache[4];
+    const int forced = env_int("ERSD_FORCE_BLOCKS", 0);  // tests only
+    if (forced > 0) return forced > (int)kMaxBlocks ? (int)kMaxBlocks : forced;
+    if (dt == ERSD_F32) return vec ? resident_blocks(race_kernel<ERSD_F32, true>, cache[0])
+                                   : resident_blocks(race_kernel<ERSD_F32, false>, cache[1]);
+    return vec ? resident_blocks(race_kernel<ERSD_BF16, true>, cache[2])
+               : resident_blocks(race_kernel<ERSD_BF16, false>, cache[3]);
+}
+
+// The partition both stages use.  It depends on the device (resident workgroups), so both stages recompute it
+// the same way; `nslot` is capped by what the workspace was sized for.
+int plan_part(const Geometry& g, ersd_dtype dt, size_t ws_bytes, Part& p) {
+    if (ws_bytes < workspace_for(g)) return ERSD_ERR_WORKSPACE_TOO_SMALL;
+    const int blocks = race_blocks(dt, (g.V % 8) == 0);
+    if (blocks < 1) return ERSD_ERR_HIP;
+    p = make_part(g, (uint32_t)blocks);
+    return ERSD_OK;
+}
+
 int launch_races(const void* dl, const void* tl, ersd_dtype dt, const Geometry& g, float T, uint64_t seed, void* ws,
                  size_t ws_bytes, void* stream) {
-    const Plan p = make_plan((int64_t)g.B * g.m * g.kt, g.V);
-    if (ws_bytes < workspace_for(p)) return ERSD_ERR_WORKSPACE_TOO_SMALL;
-
     RaceArgs a;
+    const int rc = plan_part(g, dt, ws_bytes, a.part);
+    if (rc != ERSD_OK) return rc;
     a.draft = static_cast<const char*>(dl);
     a.target = static_cast<const char*>(tl);
-    a.partials = static_cast<Partial*>(ws);
+    a.out = static_cast<SegOut*>(ws);
     a.V = g.V;
-    a.kd = g.kd;
-    a.kt = g.kt;
     a.m = g.m;
-    a.nsplit = p.nsplit;
-    a.chunk = p.chunk;
     a.key0 = (uint32_t)(seed & 0xffffffffu);
     a.key1 = (uint32_t)(seed >> 32);
     a.T = (double)T;
     a.c2 = (float)(1.4426950408889634 / (double)T);
+    const char* mode = std::getenv("ERSD_KERNEL");  // tests only: "exhaustive" scores every token in fp64
+    a.exhaustive = mode && std::strcmp(mode, "exhaustive") == 0;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const dim3 grid((uint32_t)(p.rows * p.nsplit)), block(kThreads);
+    const dim3 grid(a.part.G), block(kThreads);
     const bool vec = (g.V % 8) == 0;
-    const char* mode = std::getenv("ERSD_KERNEL");  // tests only: "exhaustive" scores every token in fp64
-    const bool exhaustive = mode && std::strcmp(mode, "exhaustive") == 0;
-    if (exhaustive) {
-        if (dt == ERSD_F32) hipLaunchKernelGGL(race_exhaustive_kernel<ERSD_F32>, grid, block, 0, s, a);
-        else hipLaunchKernelGGL(race_exhaustive_kernel<ERSD_BF16>, grid, block, 0, s, a);
-    } else if (dt == ERSD_F32) {
-        if (vec) hipLaunchKernelGGL((race_filtered_kernel<ERSD_F32, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((race_filtered_kernel<ERSD_F32, false>), grid, block, 0, s, a);
+    if (dt == ERSD_F32) {
+        if (vec) hipLaunchKernelGGL((race_kernel<ERSD_F32, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((race_kernel<ERSD_F32, false>), grid, block, 0, s, a);
     } else {
-        if (vec) hipLaunchKernelGGL((race_filtered_kernel<ERSD_BF16, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((race_filtered_kernel<ERSD_BF16, false>), grid, block, 0, s, a);
+        if (vec) hipLaunchKernelGGL((race_kernel<ERSD_BF16, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((race_kernel<ERSD_BF16, false>), grid, block, 0, s, a);
     }
     return hipGetLastError() == hipSuccess ? ERSD_OK : ERSD_ERR_HIP;
 }
 
-int launch_finish(int variant, const Geometry& g, const int32_t* parent, int32_t* dtok, int32_t* ttok, int32_t* acc,
-                  int32_t* best_draft, int32_t* best_len, int32_t* accept_node, const void* ws, size_t ws_bytes,
-                  void* stream) {
-    const Plan p = make_plan((int64_t)g.B * g.m * g.kt, g.V);
-    if (ws_bytes < workspace_for(p)) return ERSD_ERR_WORKSPACE_TOO_SMALL;
+int launch_finish(int variant, const Geometry& g, ersd_dtype dt, float T, const int32_t* parent, int32_t* dtok,
+                  int32_t* ttok,
+                  int32_t* acc, int32_t* best_draft, int32_t* best_len, int32_t* accept_node, const void* ws,
+                  size_t ws_bytes, void* stream) {
     FinishArgs f;
-    f.partials = static_cast<const Partial*>(ws);
-    f.nsplit = p.nsplit;
-    f.kd = g.kd;
-    f.kt = g.kt;
+    const int rc = plan_part(g, dt, ws_bytes, f.part);
+    if (rc != ERSD_OK) return rc;
+    f.out = static_cast<const SegOut*>(ws);
+    f.T = (double)T;
     f.m = g.m;
     f.variant = variant;
     f.parent = parent;
@@ -708,7 +1021,15 @@ int launch_finish(int variant, const Geometry& g, const int32_t* parent, int32_t
     f.best_draft = best_draft;
     f.best_len = best_len;
     f.accept_node = accept_node;
-    hipLaunchKernelGGL(finish_kernel, dim3((uint32_t)g.B), dim3(kThreads), 0, static_cast<hipStream_t>(stream), f);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint64_t items = f.part.rows * 2;
+    if ((uint64_t)g.m * g.kt * 2 <= 2 * (kThreads / 8)) {  // at most two passes per prompt: one launch
+        hipLaunchKernelGGL(finish_kernel, dim3((uint32_t)g.B), dim3(kThreads), 0, s, f);
+    } else {
+        hipLaunchKernelGGL(resolve_kernel, dim3((uint32_t)((items + kThreads / 8 - 1) / (kThreads / 8))),
+                           dim3(kThreads), 0, s, f);
+        hipLaunchKernelGGL(accept_kernel, dim3((uint32_t)g.B), dim3(kThreads), 0, s, f);
+    }
     return hipGetLastError() == hipSuccess ? ERSD_OK : ERSD_ERR_HIP;
 }
 
@@ -717,7 +1038,8 @@ int launch(const void* dl, const void* tl, ersd_dtype dt, const Geometry& g, flo
            int32_t* accept_node, void* ws, size_t ws_bytes, void* stream) {
     const int rc = launch_races(dl, tl, dt, g, T, seed, ws, ws_bytes, stream);
     if (rc != ERSD_OK) return rc;
-    return launch_finish(variant, g, parent, dtok, ttok, acc, best_draft, best_len, accept_node, ws, ws_bytes, stream);
+    return launch_finish(variant, g, dt, T, parent, dtok, ttok, acc, best_draft, best_len, accept_node, ws, ws_bytes,
+                         stream);
 }
 
 }  // namespace
@@ -728,7 +1050,7 @@ size_t ersd_race_workspace_bytes(int variant, int32_t B, int32_t m, int32_t k_or
     if (dt != ERSD_F32 && dt != ERSD_BF16) return 0;
     Geometry g;
     if (!geometry(variant, B, m, k_or_N, V, g)) return 0;
-    return workspace_for(make_plan((int64_t)g.B * g.m * g.kt, g.V));
+    return workspace_for(g);
 }
 
 int ersd_race_stage_races(int variant, const void* draft_logits, const void* target_logits, ersd_dtype dt, int32_t B,
@@ -739,23 +1061,27 @@ int ersd_race_stage_races(int variant, const void* draft_logits, const void* tar
     if (rc != ERSD_OK) return rc;
     Geometry g;
     if (!geometry(variant, B, m, k_or_N, V, g)) return ERSD_ERR_INVALID_ARG;
+    if (workspace_bytes < workspace_for(g)) return ERSD_ERR_WORKSPACE_TOO_SMALL;
     return launch_races(draft_logits, target_logits, dt, g, temperature, seed, workspace, workspace_bytes, stream);
 }
 
-int ersd_race_stage_accept(int variant, int32_t B, int32_t m, int32_t k_or_N, int32_t V, const int32_t* parent,
-                           int32_t* draft_tokens, int32_t* target_tokens, int32_t* accept_len, int32_t* best_draft,
-                           int32_t* best_len, int32_t* accept_node, const void* workspace, size_t workspace_bytes,
-                           void* stream) {
+int ersd_race_stage_accept(int variant, ersd_dtype dt, int32_t B, int32_t m, int32_t k_or_N, int32_t V,
+                           float temperature, const int32_t* parent, int32_t* draft_tokens, int32_t* target_tokens, int32_t* accept_len,
+                           int32_t* best_draft, int32_t* best_len, int32_t* accept_node, const void* workspace,
+                           size_t workspace_bytes, void* stream) {
     if (!draft_tokens || !target_tokens || !accept_len || !workspace) return ERSD_ERR_NULL_POINTER;
     if (variant == ERSD_VARIANT_TREE && !parent) return ERSD_ERR_NULL_POINTER;
     if (variant == ERSD_VARIANT_MULTI && (!best_draft || !best_len)) return ERSD_ERR_NULL_POINTER;
+    if (dt != ERSD_F32 && dt != ERSD_BF16) return ERSD_ERR_UNSUPPORTED_DTYPE;
+    if (!(temperature > 0.0f) || !std::isfinite(temperature)) return ERSD_ERR_INVALID_ARG;
     if ((uintptr_t)workspace & 15) return ERSD_ERR_MISALIGNED;
     Geometry g;
     if (!geometry(variant, B, m, k_or_N, V, g)) return ERSD_ERR_INVALID_ARG;
+    if (workspace_bytes < workspace_for(g)) return ERSD_ERR_WORKSPACE_TOO_SMALL;
     if (variant != ERSD_VARIANT_MULTI) { best_draft = nullptr; best_len = nullptr; }
     if (variant != ERSD_VARIANT_TREE) { parent = nullptr; accept_node = nullptr; }
-    return launch_finish(variant, g, parent, draft_tokens, target_tokens, accept_len, best_draft, best_len, accept_node,
-                         workspace, workspace_bytes, stream);
+    return launch_finish(variant, g, dt, temperature, parent, draft_tokens, target_tokens, accept_len, best_draft,
+                         best_len, accept_node, workspace, workspace_bytes, stream);
 }
 
 int ersd_race_verify(const void* draft_logits, const void* target_logits, ersd_dtype dt, int32_t B, int32_t k,
@@ -766,6 +1092,7 @@ int ersd_race_verify(const void* draft_logits, const void* target_logits, ersd_d
     if (rc != ERSD_OK) return rc;
     Geometry g;
     if (!geometry(ERSD_VARIANT_SEQUENCE, B, 1, k, V, g)) return ERSD_ERR_INVALID_ARG;
+    if (workspace_bytes < workspace_for(g)) return ERSD_ERR_WORKSPACE_TOO_SMALL;
     return launch(draft_logits, target_logits, dt, g, temperature, seed, ERSD_VARIANT_SEQUENCE, nullptr, draft_tokens,
                   target_tokens, accept_len, nullptr, nullptr, nullptr, workspace, workspace_bytes, stream);
 }
@@ -780,6 +1107,7 @@ int ersd_race_verify_multi(const void* draft_logits, const void* target_logits, 
     if (rc != ERSD_OK) return rc;
     Geometry g;
     if (!geometry(ERSD_VARIANT_MULTI, B, m, k, V, g)) return ERSD_ERR_INVALID_ARG;
+    if (workspace_bytes < workspace_for(g)) return ERSD_ERR_WORKSPACE_TOO_SMALL;
     return launch(draft_logits, target_logits, dt, g, temperature, seed, ERSD_VARIANT_MULTI, nullptr, draft_tokens,
                   target_tokens, accept_len, best_draft, best_len, nullptr, workspace, workspace_bytes, stream);
 }
@@ -793,6 +1121,7 @@ int ersd_race_verify_tree(const void* draft_logits, const void* target_logits, e
     if (rc != ERSD_OK) return rc;
     Geometry g;
     if (!geometry(ERSD_VARIANT_TREE, B, 1, N, V, g)) return ERSD_ERR_INVALID_ARG;
+    if (workspace_bytes < workspace_for(g)) return ERSD_ERR_WORKSPACE_TOO_SMALL;
     return launch(draft_logits, target_logits, dt, g, temperature, seed, ERSD_VARIANT_TREE, parent, draft_tokens,
                   target_tokens, accept_len, nullptr, nullptr, accept_node, workspace, workspace_bytes, stream);
 }
@@ -805,6 +1134,25 @@ int ersd_selftest_bounds(uint64_t* counters, void* stream) {
     hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(64), 0, s, c);
     hipLaunchKernelGGL(selftest_bounds_kernel, dim3(256 * 16), dim3(kThreads), 0, s, c);
     return hipGetLastError() == hipSuccess ? ERSD_OK : ERSD_ERR_HIP;
+}
+
+int ersd_plan_describe_host(int variant, int32_t B, int32_t m, int32_t k_or_N, int32_t V, uint32_t blocks,
+                            uint32_t* out_G, uint32_t* out_nslot, uint64_t* block_start, uint32_t* row_first,
+                            uint32_t* row_last) {
+    Geometry g;
+    if (!out_G || !out_nslot) return ERSD_ERR_NULL_POINTER;
+    if (blocks < 1 || blocks > kMaxBlocks || !geometry(variant, B, m, k_or_N, V, g)) return ERSD_ERR_INVALID_ARG;
+    const Part p = make_part(g, blocks);
+    *out_G = p.G;
+    *out_nslot = p.nslot;
+    if (block_start)
+        for (uint32_t b = 0; b <= p.G; ++b) block_start[b] = part_start_pos(p, b);
+    if (row_first && row_last)
+        for (uint64_t r = 0; r < p.rows; ++r) {
+            row_first[r] = part_first_block(p, r);
+            row_last[r] = part_last_block(p, r);
+        }
+    return ERSD_OK;
 }
 
 int ersd_tree_validate_host(const int32_t* parent_host, int32_t N) {
@@ -827,6 +1175,6 @@ const char* ersd_status_string(int status) {
     }
 }
 
-int ersd_version(void) { return 100; }
+int ersd_version(void) { return 200; }
 
 }  // extern "C"

@@ -44,7 +44,10 @@ def lib():
         L.ersd_race_verify_tree.restype = ctypes.c_int
         L.ersd_race_stage_races.argtypes = [ctypes.c_int, vp, vp, ctypes.c_int, i32, i32, i32, i32, f32, u64, vp, sz, vp]
         L.ersd_race_stage_races.restype = ctypes.c_int
-        L.ersd_race_stage_accept.argtypes = [ctypes.c_int, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.ersd_race_stage_accept.argtypes = [ctypes.c_int, ctypes.c_int, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp,
+                                             vp, vp, sz, vp]
+        L.ersd_plan_describe_host.argtypes = [ctypes.c_int, i32, i32, i32, i32, ctypes.c_uint32, vp, vp, vp, vp, vp]
+        L.ersd_plan_describe_host.restype = ctypes.c_int
         L.ersd_race_stage_accept.restype = ctypes.c_int
         L.ersd_selftest_bounds.argtypes = [vp, vp]
         L.ersd_selftest_bounds.restype = ctypes.c_int
@@ -241,7 +244,8 @@ class PreparedVerify:
                                        self.V, self.temperature, self.seed, p(self.workspace), self.ws_bytes, st))
         if mid_event is not None:
             mid_event.record()
-        _check(L.ersd_race_stage_accept(self.variant, self.B, self.m, self.kn, self.V, p(self.parent),
+        _check(L.ersd_race_stage_accept(self.variant, self.code, self.B, self.m, self.kn, self.V, self.temperature,
+                                        p(self.parent),
                                         p(self.draft_tokens), p(self.target_tokens), p(self.accept_len),
                                         p(self.best_draft), p(self.best_len), p(self.accept_node), p(self.workspace),
                                         self.ws_bytes, st))
@@ -256,6 +260,19 @@ def selftest_bounds(device="cuda"):
     h = c.cpu()
     as_float = lambda v: torch.tensor([int(v)], dtype=torch.int32).view(torch.float32).item()
     return dict(bad_upper=int(h[0]), bad_refine=int(h[1]), max_refine_err=as_float(h[2]), max_upper_slack=as_float(h[3]))
+
+
+def plan_describe(variant, B, m, k_or_N, V, blocks):
+    """Host-only view of the work partition -> dict(G, nslot, block_start [G+1], row_first [rows], row_last [rows])."""
+    import numpy as np
+    rows = B * (m if variant == VARIANT_MULTI else 1) * (k_or_N if variant == VARIANT_TREE else k_or_N + 1)
+    G, nslot = ctypes.c_uint32(0), ctypes.c_uint32(0)
+    start = np.zeros(blocks + 1, dtype=np.uint64)
+    first = np.zeros(rows, dtype=np.uint32)
+    last = np.zeros(rows, dtype=np.uint32)
+    _check(lib().ersd_plan_describe_host(variant, B, m, k_or_N, V, blocks, ctypes.byref(G), ctypes.byref(nslot),
+                                         start.ctypes.data, first.ctypes.data, last.ctypes.data))
+    return dict(G=G.value, nslot=nslot.value, block_start=start[: G.value + 1], row_first=first, row_last=last)
 
 
 def tree_validate_host(parent):

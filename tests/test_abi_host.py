@@ -25,13 +25,14 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(L):
     names = declared_functions()
     assert {"ersd_race_verify", "ersd_race_verify_multi", "ersd_race_verify_tree", "ersd_race_workspace_bytes",
-            "ersd_status_string", "ersd_version", "ersd_tree_validate_host", "ersd_selftest_bounds"} <= set(names)
+            "ersd_status_string", "ersd_version", "ersd_tree_validate_host", "ersd_selftest_bounds",
+            "ersd_race_stage_races", "ersd_race_stage_accept", "ersd_plan_describe_host"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
 
 
 def test_version_and_status_strings(L):
-    assert L.ersd_version() >= 100
+    assert L.ersd_version() >= 200
     seen = set()
     for s in range(0, -7, -1):
         txt = L.ersd_status_string(s)
@@ -56,7 +57,7 @@ def test_sequence_argument_errors(L):
         assert seq_call(L, T=T) == -2
     assert seq_call(L, B=0) == -2 and seq_call(L, k=0) == -2 and seq_call(L, V=0) == -2 and seq_call(L, B=-3) == -2
     assert seq_call(L, k=2**31 - 1) == -2                     # k + 1 would overflow
-    assert seq_call(L, B=2**20, k=2**12, V=8) == -2           # too many rows for the grid
+    assert seq_call(L, B=2**30, k=2**12, V=2**20) == -2       # job too large for the 64-bit work partition
     assert seq_call(L, d=FAKE + 4) == -4 and seq_call(L, t=FAKE + 8) == -4 and seq_call(L, ws=FAKE + 2) == -4
     assert seq_call(L, wsb=8) == -5
 
@@ -81,6 +82,17 @@ def test_multi_and_tree_argument_errors(L):
     assert tree(parent=None) == -1 and tree(N=0) == -2 and tree(T=-2.0) == -2 and tree(wsb=1) == -5
     assert tree(o=[FAKE, FAKE, None, FAKE]) == -1
     assert L.ersd_selftest_bounds(None, None) == -1
+    # the two stages validate like the verify calls
+    assert L.ersd_race_stage_races(0, None, FAKE, 0, 1, 1, 2, 64, 1.0, 0, FAKE, 1 << 30, None) == -1
+    assert L.ersd_race_stage_races(0, FAKE, FAKE, 0, 1, 1, 2, 64, 0.0, 0, FAKE, 1 << 30, None) == -2
+    assert L.ersd_race_stage_races(7, FAKE, FAKE, 0, 1, 1, 2, 64, 1.0, 0, FAKE, 1 << 30, None) == -2
+    assert L.ersd_race_stage_races(0, FAKE, FAKE, 0, 1, 1, 2, 64, 1.0, 0, FAKE, 8, None) == -5
+    assert L.ersd_race_stage_accept(0, 0, 1, 1, 2, 64, 1.0, None, FAKE, FAKE, FAKE, None, None, None, FAKE, 8, None) == -5
+    assert L.ersd_race_stage_accept(0, 0, 1, 1, 2, 64, 1.0, None, None, FAKE, FAKE, None, None, None, FAKE, 1 << 30, None) == -1
+    assert L.ersd_race_stage_accept(2, 0, 1, 1, 2, 64, 1.0, None, FAKE, FAKE, FAKE, None, None, None, FAKE, 1 << 30, None) == -1
+    assert L.ersd_race_stage_accept(1, 0, 1, 1, 2, 64, 1.0, None, FAKE, FAKE, FAKE, None, None, None, FAKE, 1 << 30, None) == -1
+    assert L.ersd_race_stage_accept(0, 9, 1, 1, 2, 64, 1.0, None, FAKE, FAKE, FAKE, None, None, None, FAKE, 1 << 30, None) == -3
+    assert L.ersd_race_stage_accept(0, 0, 1, 1, 2, 64, 0.0, None, FAKE, FAKE, FAKE, None, None, None, FAKE, 1 << 30, None) == -2
 
 
 def test_workspace_bytes(L):

@@ -21,17 +21,17 @@ def race():
 
 @pytest.fixture(autouse=True)
 def clean_env():
-    for k in ("ERSD_FORCE_SPLIT", "ERSD_KERNEL"):
+    for k in ("ERSD_FORCE_BLOCKS", "ERSD_KERNEL"):
         os.environ.pop(k, None)
     yield
-    for k in ("ERSD_FORCE_SPLIT", "ERSD_KERNEL"):
+    for k in ("ERSD_FORCE_BLOCKS", "ERSD_KERNEL"):
         os.environ.pop(k, None)
 
 
 def run_case(race, oracle_mod, w, split=0, kernel=None, note=""):
     print(f"[case] {wl.describe(w)} split={split} kernel={kernel} {note}", flush=True)
     if split:
-        os.environ["ERSD_FORCE_SPLIT"] = str(split)
+        os.environ["ERSD_FORCE_BLOCKS"] = str(split)
     if kernel:
         os.environ["ERSD_KERNEL"] = kernel
     inp = wl.make_inputs(w, "cuda")
@@ -55,7 +55,7 @@ def run_case(race, oracle_mod, w, split=0, kernel=None, note=""):
         ex = parity.check_tree(gpu, ora, oracle_mod, d_host, t_host, par, T, seed)
     flagged = int(ora["draft_info"]["near_tie"].sum() + ora["target_info"]["near_tie"].sum())
     print(f"[case] ok: oracle near-tie rows {flagged}, exempted rows {ex}", flush=True)
-    os.environ.pop("ERSD_FORCE_SPLIT", None)
+    os.environ.pop("ERSD_FORCE_BLOCKS", None)
     os.environ.pop("ERSD_KERNEL", None)
     return gpu, ora, ex
 
@@ -83,7 +83,7 @@ SMALL = [
 
 @pytest.mark.parametrize("w", SMALL, ids=lambda w: f"{w.name}-V{w.V}")
 @pytest.mark.parametrize("kernel", ["exhaustive", None], ids=["exhaustive", "filtered"])
-@pytest.mark.parametrize("split", [0, 1, 3])
+@pytest.mark.parametrize("split", [0, 1, 3, 50])
 def test_small_shapes_match_oracle(race, oracle_mod, w, kernel, split):
     run_case(race, oracle_mod, w, split=split, kernel=kernel)
 
@@ -92,9 +92,9 @@ def test_results_do_not_depend_on_split_or_kernel_and_are_deterministic(race):
     w = wl.shrink(wl.WORKLOADS[1], B=4, k=4, V=40000)
     inp = wl.make_inputs(w, "cuda")
     ref = None
-    for split in (0, 1, 2, 5, 19):
+    for split in (0, 1, 2, 5, 19, 300):
         for kernel in (None, "exhaustive"):
-            os.environ["ERSD_FORCE_SPLIT"] = str(split)
+            os.environ["ERSD_FORCE_BLOCKS"] = str(split)
             if kernel:
                 os.environ["ERSD_KERNEL"] = kernel
             else:
@@ -114,11 +114,11 @@ def test_degenerate_rows(race, oracle_mod):
     d, t, a = race.race_verify(one[:, :2].contiguous(), one, 1.0, 0)
     assert (t == 0).all() and (a == 2).all()
     ninf = torch.full((2, 3, 4104), float("-inf"), device=dev)
-    for split in (1, 2):
-        os.environ["ERSD_FORCE_SPLIT"] = str(split)
+    for split in (1, 2, 6):
+        os.environ["ERSD_FORCE_BLOCKS"] = str(split)
         d, t, a = race.race_verify(ninf[:, :2].contiguous(), ninf, 1.0, 0)
         assert (t == 0).all() and (d == 0).all() and (a == 2).all()
-    os.environ.pop("ERSD_FORCE_SPLIT")
+    os.environ.pop("ERSD_FORCE_BLOCKS")
     g = torch.Generator(device=dev).manual_seed(5)
     V = 30000
     target = 3 * torch.randn(2, 4, V, generator=g, device=dev)
@@ -159,19 +159,19 @@ def test_exact_score_ties_go_to_lowest_index(race, oracle_mod):
     equal logits on a pair of tokens whose words coincide cannot be constructed without inverting the generator,
     so the reachable case is used: two equal huge logits dominate any exponential, the race between them is decided
     by their own words, and the GPU must agree with the oracle including when they sit in different splits."""
-    V = 20480
+    V = 40960
     row = torch.full((V,), -50.0)
     row[100] = 40.0
-    row[20000] = 40.0
+    row[40000] = 40.0
     target = row.repeat(1, 2, 1).contiguous().cuda()
     draft = row.repeat(1, 1, 1).contiguous().cuda()
-    for split in (1, 4):
-        os.environ["ERSD_FORCE_SPLIT"] = str(split)
+    for split in (1, 9):
+        os.environ["ERSD_FORCE_BLOCKS"] = str(split)
         for seed in range(6):
             gpu = race.race_verify(draft, target, 1.0, seed)
             ora = oracle_mod.race_verify(draft.cpu(), target.cpu(), 1.0, seed, want_info=True)
             parity.check_sequence(gpu, ora, oracle_mod, draft.cpu(), target.cpu(), 1.0, seed)
-            assert int(gpu[1][0, 0]) in (100, 20000)
+            assert int(gpu[1][0, 0]) in (100, 40000)
 
 
 def test_tree_contract_on_device(race, oracle_mod):

@@ -1,0 +1,63 @@
+"""The balanced work partition, checked on the host by brute force: shares tile the job exactly, every row's
+writers are exactly the shares that overlap it, and the slot bound the workspace is sized for holds."""
+import numpy as np
+import pytest
+
+from paper_2504_15475_amd import race
+
+SEQ, MULTI, TREE = race.VARIANT_SEQUENCE, race.VARIANT_MULTI, race.VARIANT_TREE
+
+CASES = [
+    (SEQ, 1, 1, 4, 32000), (SEQ, 64, 1, 8, 128256), (SEQ, 256, 1, 16, 152064), (MULTI, 32, 8, 8, 128256),
+    (TREE, 16, 1, 64, 256000), (SEQ, 3, 1, 2, 4999), (SEQ, 2, 1, 1, 7), (TREE, 5, 1, 3, 100001), (MULTI, 2, 3, 2, 6152),
+    (SEQ, 1, 1, 1, 1), (SEQ, 7, 1, 5, 81920),
+]
+
+
+@pytest.mark.parametrize("variant,B,m,k,V", CASES)
+@pytest.mark.parametrize("blocks", [1, 2, 7, 300, 1792, 2048, 4096])
+def test_partition_invariants(variant, B, m, k, V, blocks):
+    d = race.plan_describe(variant, B, m, k, V, blocks)
+    G, nslot, start = d["G"], d["nslot"], d["block_start"].astype(np.int64)
+    kt = k if variant == TREE else k + 1
+    mm = m if variant == MULTI else 1
+    rows = B * mm * kt
+    V8 = (V + 7) // 8
+    assert 1 <= G <= blocks and len(start) == G + 1
+    assert start[0] == 0 and start[-1] == rows * V8
+    assert (np.diff(start) > 0).all()                      # no empty share
+    # brute force: which shares overlap each row
+    first_bf = np.searchsorted(start, np.arange(rows) * V8, side="right") - 1
+    last_bf = np.searchsorted(start, (np.arange(rows) + 1) * V8 - 1, side="right") - 1
+    assert np.array_equal(first_bf, d["row_first"].astype(np.int64))
+    assert np.array_equal(last_bf, d["row_last"].astype(np.int64))
+    assert (last_bf - first_bf + 1).max() <= nslot
+    # balance: shares differ by at most one group's worth of cost (weights 5 per pair group, 3 per single)
+    if G > 1 and variant != TREE:
+        kd = k
+        def cost(lo, hi):      # cost of global groups [lo, hi)
+            c = 0
+            pos = lo
+            while pos < hi:
+                row = pos // V8
+                nxt = min(hi, (row + 1) * V8)
+                c += (nxt - pos) * (5 if (row % kt) < kd else 3)
+                pos = nxt
+            return c
+        costs = [cost(int(start[b]), int(start[b + 1])) for b in range(0, G, max(1, G // 50))]
+        assert max(costs) - min(costs) <= 12
+    # the workspace covers the slots of any workgroup count the library may choose
+    need = race.workspace_bytes(variant, B, m, k, V, race.ERSD_BF16)
+    assert need >= rows * 2 * nslot * 16
+
+
+def test_plan_rejects_bad_arguments():
+    L = race.lib()
+    import ctypes
+    G, ns = ctypes.c_uint32(), ctypes.c_uint32()
+    assert L.ersd_plan_describe_host(0, 1, 1, 4, 32000, 0, ctypes.byref(G), ctypes.byref(ns), None, None, None) == -2
+    assert L.ersd_plan_describe_host(0, 1, 1, 4, 32000, 5000, ctypes.byref(G), ctypes.byref(ns), None, None, None) == -2
+    assert L.ersd_plan_describe_host(0, 0, 1, 4, 32000, 8, ctypes.byref(G), ctypes.byref(ns), None, None, None) == -2
+    assert L.ersd_plan_describe_host(0, 1, 1, 4, 32000, 8, None, ctypes.byref(ns), None, None, None) == -1
+    assert L.ersd_plan_describe_host(0, 1, 1, 4, 32000, 8, ctypes.byref(G), ctypes.byref(ns), None, None, None) == 0
+    assert G.value >= 1
