@@ -39,8 +39,14 @@
 
 namespace {
 
-constexpr int kThreads = 256;                       // 4 wavefronts per workgroup
-constexpr int kGroup = 8;                           // tokens a lane filters at a time: two Philox calls
+#ifndef ERSD_THREADS
+#define ERSD_THREADS 256
+#endif
+constexpr int kThreads = ERSD_THREADS;              // wavefronts per workgroup: kThreads / 64
+#ifndef ERSD_STAGES
+#define ERSD_STAGES 2
+#endif
+constexpr int kStages = ERSD_STAGES;                // register buffers per row: kStages - 1 tiles of loads in flight
 constexpr int kListCap = 512;                       // candidate slots per side per workgroup
 constexpr int kWave = 64;
 constexpr int kWaves = kThreads / kWave;
@@ -227,37 +233,41 @@ struct Raw {  // 8 logits as loaded: bf16 -> a only (4 dwords); fp32 (or element
 
 constexpr uint32_t kNegInfF32 = 0xFF800000u;
 
-// Tokens one lane loads per tile: 32 bytes per row when rows are read with 128-bit loads.
+// Geometry of a tile.  With 128-bit loads every lane takes two 16-byte pieces per row and tile, and the pieces
+// are laid out so that each load instruction of a wavefront covers one contiguous kilobyte: lane t reads piece t
+// and piece kThreads + t of the tile.  The element-load path gives a lane 8 consecutive tokens instead.
 template <int DT, bool VEC>
 struct TileShape {
-    static constexpr int kTokPerThread = (VEC && DT == ERSD_BF16) ? 16 : 8;
+    static constexpr int kTokPerPiece = VEC ? (DT == ERSD_BF16 ? 8 : 4) : 4;
+    static constexpr int kTokPerThread = 2 * kTokPerPiece;
     static constexpr int kTile = kThreads * kTokPerThread;
+    __device__ static __forceinline__ int32_t piece_a(int32_t tile_base, int tid) {
+        return tile_base + tid * (VEC ? kTokPerPiece : kTokPerThread);
+    }
+    __device__ static __forceinline__ int32_t piece_b(int32_t tile_base, int tid) {
+        return VEC ? tile_base + (kThreads + tid) * kTokPerPiece : tile_base + tid * kTokPerThread + kTokPerPiece;
+    }
 };
 
+// The two pieces of one lane: tokens [ia, ia + kTokPerPiece) and [ib, ib + kTokPerPiece).
 template <int DT, bool VEC>
-__device__ __forceinline__ Raw load_raw(const char* row, int32_t i0, int32_t end) {
+__device__ __forceinline__ Raw load_raw(const char* row, int32_t ia, int32_t ib, int32_t end) {
     Raw r;
     if (VEC) {
-        // Two unconditional 128-bit loads (no branch, so the compiler can count loads in flight exactly).  i0 and
-        // end are multiples of 8 and the segment is not empty; groups past the end re-read the segment's last
-        // group instead, and the refine step never accepts a token index >= end.
-        const int32_t last = end - kGroup;
-        if (DT == ERSD_BF16) {
-            const int32_t ia = i0 < last ? i0 : last;
-            const int32_t ib = i0 + kGroup < last ? i0 + kGroup : last;
-            r.a = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + (size_t)ia * 2));
-            r.b = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + (size_t)ib * 2));
-        } else {
-            const int32_t ia = i0 < last ? i0 : last;
-            const u32x4* p = reinterpret_cast<const u32x4*>(row + (size_t)ia * 4);
-            r.a = __builtin_nontemporal_load(p);
-            r.b = __builtin_nontemporal_load(p + 1);
-        }
+        // Two unconditional 128-bit loads (no branch, so the compiler can count loads in flight exactly).  Piece
+        // starts and `end` are multiples of the piece size and the segment is not empty; pieces past the end
+        // re-read the segment's last piece instead, and the refine step never accepts a token index >= end.
+        constexpr int es = DT == ERSD_BF16 ? 2 : 4;
+        const int32_t last = end - TileShape<DT, VEC>::kTokPerPiece;
+        const int32_t ca = ia < last ? ia : last;
+        const int32_t cb = ib < last ? ib : last;
+        r.a = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + (size_t)ca * es));
+        r.b = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + (size_t)cb * es));
     } else {  // element loads; registers hold fp32 bit patterns
         uint32_t f[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const int32_t i = i0 + e;
+            const int32_t i = e < 4 ? ia + e : ib + e - 4;
             f[e] = i < end ? __float_as_uint(widen_elem(row, DT, i)) : kNegInfF32;
         }
         r.a = u32x4{f[0], f[1], f[2], f[3]};
@@ -373,7 +383,8 @@ __device__ __forceinline__ float raw_logit_const(const Raw& r, int e) {
 // The rare second look at a lane's 8 tokens: those whose upper bound reaches tau get an fp32 score with an error
 // margin; what can still be the maximum goes to the candidate list and raises tau (lane, wavefront, workgroup).
 template <bool RAWF32, bool HASQ>
-__device__ __forceinline__ void refine_tile(Lds& lds, float c2, int32_t i0, int32_t end, const Raw& rq, const Raw& rp,
+__device__ __forceinline__ void refine_tile(Lds& lds, float c2, int32_t i0, int32_t i1, int32_t end, const Raw& rq,
+                                            const Raw& rp,
                                             const uint32_t (&x)[8], bool flag, float tauq_m, float taup_m,
                                             float& tauq, float& taup) {
     if (!flag) return;
@@ -391,7 +402,7 @@ __device__ __forceinline__ void refine_tile(Lds& lds, float c2, int32_t i0, int3
         mask &= mask - 1;
         const int e = b & 7;
         const bool isq = HASQ && b >= 8;
-        const int32_t idx = i0 + e;
+        const int32_t idx = e < 4 ? i0 + e : i1 + e - 4;
         if (idx < end) {
             const uint32_t xe = e < 4 ? pick4(u32x4{x[0], x[1], x[2], x[3]}, e) : pick4(u32x4{x[4], x[5], x[6], x[7]}, e - 4);
             const float lq = HASQ ? raw_logit<RAWF32>(rq, e) : 0.0f;
@@ -409,8 +420,8 @@ __device__ __forceinline__ void refine_tile(Lds& lds, float c2, int32_t i0, int3
 
 // The per-iteration work of one lane: 8 tokens of one or two rows.
 template <bool RAWF32, bool HASQ>
-__device__ __forceinline__ void filter_tile(const RaceArgs& a, const Seg& c, Lds& lds, int32_t i0, const Raw& rq,
-                                            const Raw& rp, float& tauq, float& taup) {
+__device__ __forceinline__ void filter_tile(const RaceArgs& a, const Seg& c, Lds& lds, int32_t i0, int32_t i1,
+                                            const Raw& rq, const Raw& rp, float& tauq, float& taup) {
     const float c2 = a.c2;
     // the workgroup's bound, possibly raised by another wavefront since the last iteration
     taup = fmaxf(taup, lds_tau(lds, 1));
@@ -419,8 +430,8 @@ __device__ __forceinline__ void filter_tile(const RaceArgs& a, const Seg& c, Lds
     const float tauq_m = HASQ ? with_margin(tauq) : 0.0f;
 
     uint32_t x[8];
-    philox4x32_10((uint32_t)i0 >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, x);
-    philox4x32_10(((uint32_t)i0 >> 2) + 1, c.c1, c.c2, c.c3, a.key0, a.key1, x + 4);
+    philox4x32_10((uint32_t)i0 >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, x);      // tokens i0 .. i0 + 3
+    philox4x32_10((uint32_t)i1 >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, x + 4);  // tokens i1 .. i1 + 3
     float lp[8], lq[8];
     unpack<RAWF32>(rp, lp);
     if (HASQ) unpack<RAWF32>(rq, lq);
@@ -436,38 +447,47 @@ __device__ __forceinline__ void filter_tile(const RaceArgs& a, const Seg& c, Lds
     if (HASQ) flag = flag || (accq >= tauq_m);
 
     if (__builtin_amdgcn_ballot_w64(flag) != 0)  // rare: some lane holds a token that may matter
-        refine_tile<RAWF32, HASQ>(lds, c2, i0, c.end, rq, rp, x, flag, tauq_m, taup_m, tauq, taup);
+        refine_tile<RAWF32, HASQ>(lds, c2, i0, i1, c.end, rq, rp, x, flag, tauq_m, taup_m, tauq, taup);
 }
 
-// One lane's share of a tile: 8 tokens, or 16 as two groups of 8 when the registers hold bf16.
+// One lane's share of a tile: its two pieces.  A bf16 piece is 8 tokens and is filtered on its own; two fp32
+// pieces (or the 8 consecutive tokens of the element-load path) make one group of 8.
 template <int DT, bool VEC, bool HASQ>
-__device__ __forceinline__ void filter_lane(const RaceArgs& a, const Seg& c, Lds& lds, int32_t i0, const Raw& rq,
-                                            const Raw& rp, float& tauq, float& taup) {
+__device__ __forceinline__ void filter_lane(const RaceArgs& a, const Seg& c, Lds& lds, int32_t ia, int32_t ib,
+                                            const Raw& rq, const Raw& rp, float& tauq, float& taup) {
     constexpr bool RAWF32 = (DT == ERSD_F32) || !VEC;
-    if (TileShape<DT, VEC>::kTokPerThread == 16) {
+    if (VEC && DT == ERSD_BF16) {
         Raw hq, hp;
         hq.a = rq.a; hq.b = rq.a; hp.a = rp.a; hp.b = rp.a;
-        filter_tile<RAWF32, HASQ>(a, c, lds, i0, hq, hp, tauq, taup);
+        filter_tile<RAWF32, HASQ>(a, c, lds, ia, ia + 4, hq, hp, tauq, taup);
         hq.a = rq.b; hq.b = rq.b; hp.a = rp.b; hp.b = rp.b;
-        filter_tile<RAWF32, HASQ>(a, c, lds, i0 + kGroup, hq, hp, tauq, taup);
+        filter_tile<RAWF32, HASQ>(a, c, lds, ib, ib + 4, hq, hp, tauq, taup);
     } else {
-        filter_tile<RAWF32, HASQ>(a, c, lds, i0, rq, rp, tauq, taup);
+        filter_tile<RAWF32, HASQ>(a, c, lds, ia, ib, rq, rp, tauq, taup);
     }
 }
 
 template <int DT, bool VEC, bool HASQ>
 __device__ void filter_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
     constexpr bool RAWF32 = (DT == ERSD_F32) || !VEC;
-    constexpr int kTokPerThread = TileShape<DT, VEC>::kTokPerThread;
-    constexpr int kTile = TileShape<DT, VEC>::kTile;
+    typedef TileShape<DT, VEC> TS;
+    constexpr int kTile = TS::kTile;
     const int tid = threadIdx.x;
     const float c2 = a.c2;
 
-    // first tile's loads go out before anything else; the bootstrap below reads them
-    Raw qa, pa, qb, pb;
-    const int32_t first = c.begin + tid * kTokPerThread;
-    pa = load_raw<DT, VEC>(c.prow, first, c.end);
-    if (HASQ) qa = load_raw<DT, VEC>(c.qrow, first, c.end);
+    // The loads of the first kStages - 1 tiles go out before anything else (the bootstrap below reads the first).
+    // Memory latency is several microseconds under load while one wavefront filters a tile in well under one, so
+    // every wavefront keeps kStages - 1 tiles in flight in a ring of register buffers.
+    Raw q[kStages], pr[kStages];
+    const int32_t first = TS::piece_a(c.begin, tid);
+#pragma unroll
+    for (int st = 0; st < kStages - 1; ++st) {
+        const int32_t tb = c.begin + st * kTile;
+        pr[st] = load_raw<DT, VEC>(c.prow, TS::piece_a(tb, tid), TS::piece_b(tb, tid), c.end);
+        if (HASQ) q[st] = load_raw<DT, VEC>(c.qrow, TS::piece_a(tb, tid), TS::piece_b(tb, tid), c.end);
+    }
+    const Raw& pa = pr[0];
+    const Raw& qa = q[0];
 
     // Bootstrap: each wavefront starts from a lower bound of the maximum taken from the first two tokens of every
     // lane's first group (no barrier: the workgroup's bound in LDS is merged in at every tile).
@@ -495,16 +515,22 @@ __device__ void filter_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
         }
     }
 
-    // two tiles per trip, registers ping-pong so that a tile's loads have a whole tile of work to arrive
-    for (int32_t base = c.begin; base < c.end; base += 2 * kTile) {
-        const int32_t i0 = base + tid * kTokPerThread;
-        pb = load_raw<DT, VEC>(c.prow, i0 + kTile, c.end);
-        if (HASQ) qb = load_raw<DT, VEC>(c.qrow, i0 + kTile, c.end);
-        filter_lane<DT, VEC, HASQ>(a, c, lds, i0, qa, pa, tauq, taup);
-        if (base + kTile >= c.end) break;
-        pa = load_raw<DT, VEC>(c.prow, i0 + 2 * kTile, c.end);
-        if (HASQ) qa = load_raw<DT, VEC>(c.qrow, i0 + 2 * kTile, c.end);
-        filter_lane<DT, VEC, HASQ>(a, c, lds, i0 + kTile, qb, pb, tauq, taup);
+    // kStages tiles per trip; buffer indices are compile-time constants, so the ring stays in registers
+    for (int32_t base = c.begin; base < c.end; base += kStages * kTile) {
+        bool done = false;
+#pragma unroll
+        for (int st = 0; st < kStages; ++st) {
+            if (!done) {
+                constexpr int kAhead = kStages - 1;
+                const int nb = (st + kAhead) % kStages;  // buffer of the tile kAhead tiles ahead
+                const int32_t nt = base + (st + kAhead) * kTile, ct = base + st * kTile;
+                pr[nb] = load_raw<DT, VEC>(c.prow, TS::piece_a(nt, tid), TS::piece_b(nt, tid), c.end);
+                if (HASQ) q[nb] = load_raw<DT, VEC>(c.qrow, TS::piece_a(nt, tid), TS::piece_b(nt, tid), c.end);
+                filter_lane<DT, VEC, HASQ>(a, c, lds, TS::piece_a(ct, tid), TS::piece_b(ct, tid), q[st], pr[st], tauq,
+                                           taup);
+                done = base + (st + 1) * kTile >= c.end;  // workgroup-uniform
+            }
+        }
     }
 }
 
@@ -579,12 +605,14 @@ __device__ void race_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
     }
     __syncthreads();
     if (!common && row && half_tid == 0) {
-        const int w0 = side * 2;
+        const int w0 = side * (kWaves / 2);
         bs = lds.red_s[w0];
         bi = lds.red_i[w0];
-        const double os = lds.red_s[w0 + 1];
-        const int32_t oi = lds.red_i[w0 + 1];
-        if (oi >= 0 && (bi < 0 || better(os, oi, bs, bi))) { bs = os; bi = oi; }
+        for (int w = w0 + 1; w < w0 + kWaves / 2; ++w) {
+            const double os = lds.red_s[w];
+            const int32_t oi = lds.red_i[w];
+            if (oi >= 0 && (bi < 0 || better(os, oi, bs, bi))) { bs = os; bi = oi; }
+        }
         if (bi < 0 || !(bs > -INFINITY)) {
             out->count = 0;
         } else {
@@ -602,7 +630,7 @@ __device__ void race_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
 }
 
 #ifndef ERSD_WAVES_PER_EU
-#define ERSD_WAVES_PER_EU 4
+#define ERSD_WAVES_PER_EU 3
 #endif
 
 template <int DT, bool VEC>
