@@ -54,6 +54,10 @@ constexpr uint32_t kWPair = 5, kWSingle = 3;        // relative cost of one grou
 constexpr uint64_t kMinQuota = 64 * kWPair * 16;    // cost units a workgroup gets at least (16 pair iterations of a wave)
 constexpr uint32_t kMaxBlocks = 256 * 16;           // upper bound of resident workgroups, for workspace sizing
 
+#ifndef ERSD_PHILOX_ROUNDS
+#define ERSD_PHILOX_ROUNDS 10
+#endif
+constexpr int kPhiloxRounds = ERSD_PHILOX_ROUNDS;   // 10 is the generator's standard strength
 constexpr uint32_t kPhiloxM0 = 0xD2511F53u, kPhiloxM1 = 0xCD9E8D57u;
 constexpr uint32_t kPhiloxW0 = 0x9E3779B9u, kPhiloxW1 = 0xBB67AE85u;
 
@@ -139,7 +143,7 @@ struct RaceArgs {
 __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                               uint32_t k0, uint32_t k1, uint32_t out[4]) {
 #pragma unroll
-    for (int r = 0; r < 10; ++r) {
+    for (int r = 0; r < kPhiloxRounds; ++r) {
         const uint64_t p0 = (uint64_t)kPhiloxM0 * c0;
         const uint64_t p1 = (uint64_t)kPhiloxM1 * c2;
         const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
@@ -193,7 +197,7 @@ struct Seg {
 };
 
 struct Lds {
-    int32_t tau[2];      // ordered-int encoding of the workgroup's lower bound, per side
+    float tau[2];        // the workgroup's lower bound of the row maximum, per side (raised with LDS float max)
     int32_t count[2];    // candidates appended (may exceed kListCap: overflow)
     int32_t idx[2][kListCap];
     uint32_t word[2][kListCap];
@@ -276,8 +280,21 @@ __device__ __forceinline__ Raw load_raw(const char* row, int32_t ia, int32_t ib,
     return r;
 }
 
+// Operands the hot loop wants in vector registers: on gfx950 the simple VALU operations issue faster when none of
+// their sources is a scalar register or an inline constant, and the compiler would keep uniform values scalar.
+struct HotConsts {
+    float c2;        // log2(e) / T
+    uint32_t sh16;   // the shift count 16
+};
+__device__ __forceinline__ HotConsts make_hot_consts(float c2) {
+    HotConsts h;
+    asm volatile("v_mov_b32 %0, %1" : "=v"(h.c2) : "s"(c2));
+    asm volatile("v_mov_b32 %0, 16" : "=v"(h.sh16));
+    return h;
+}
+
 template <bool RAWF32>
-__device__ __forceinline__ void unpack(const Raw& r, float l[8]) {
+__device__ __forceinline__ void unpack(const Raw& r, float l[8], uint32_t sh16) {
     if (RAWF32) {
         l[0] = __uint_as_float(r.a.x); l[1] = __uint_as_float(r.a.y);
         l[2] = __uint_as_float(r.a.z); l[3] = __uint_as_float(r.a.w);
@@ -287,7 +304,7 @@ __device__ __forceinline__ void unpack(const Raw& r, float l[8]) {
         const uint32_t w[4] = {r.a.x, r.a.y, r.a.z, r.a.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            l[2 * e] = __uint_as_float(w[e] << 16);
+            l[2 * e] = __uint_as_float(w[e] << sh16);
             l[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
         }
     }
@@ -321,13 +338,6 @@ constexpr float kTauInit = -3.0e38f;  // below every finite score; -inf scores n
 // error bound of an fp32 score s2 (log2 units) against the true score
 __device__ __forceinline__ float refine_err(float s2) { return fmaf(fabsf(s2), kRelErr, kRefineErr); }
 
-__device__ __forceinline__ int32_t ordered_int(float f) {
-    const int32_t i = __float_as_int(f);
-    return i >= 0 ? i : i ^ 0x7fffffff;
-}
-__device__ __forceinline__ float from_ordered_int(int32_t i) {
-    return __int_as_float(i >= 0 ? i : i ^ 0x7fffffff);
-}
 __device__ __forceinline__ float with_margin(float tau) { return tau - fmaf(fabsf(tau), kRelErr, kUpperSlack); }
 
 __device__ __forceinline__ float wave_max(float v) {
@@ -337,7 +347,10 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 
 __device__ __forceinline__ float lds_tau(const Lds& lds, int side) {
-    return from_ordered_int(__hip_atomic_load(&lds.tau[side], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+    return __hip_atomic_load(&lds.tau[side], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+__device__ __forceinline__ void lds_tau_raise(Lds& lds, int side, float v) {
+    __hip_atomic_fetch_max(&lds.tau[side], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
 // One side's refine step for one token of one lane.
@@ -414,18 +427,15 @@ __device__ __forceinline__ void refine_tile(Lds& lds, float c2, int32_t i0, int3
         }
     }
     // publish what this lane learned; the other lanes merge it in at their next tile
-    if (taup > taup0) atomicMax(&lds.tau[1], ordered_int(taup));
-    if (HASQ && tauq > tauq0) atomicMax(&lds.tau[0], ordered_int(tauq));
+    if (taup > taup0) lds_tau_raise(lds, 1, taup);
+    if (HASQ && tauq > tauq0) lds_tau_raise(lds, 0, tauq);
 }
 
 // The per-iteration work of one lane: 8 tokens of one or two rows.
 template <bool RAWF32, bool HASQ>
-__device__ __forceinline__ void filter_tile(const RaceArgs& a, const Seg& c, Lds& lds, int32_t i0, int32_t i1,
-                                            const Raw& rq, const Raw& rp, float& tauq, float& taup) {
-    const float c2 = a.c2;
-    // the workgroup's bound, possibly raised by another wavefront since the last iteration
-    taup = fmaxf(taup, lds_tau(lds, 1));
-    if (HASQ) tauq = fmaxf(tauq, lds_tau(lds, 0));
+__device__ __forceinline__ void filter_tile(const RaceArgs& a, const Seg& c, Lds& lds, const HotConsts& h, int32_t i0,
+                                            int32_t i1, const Raw& rq, const Raw& rp, float& tauq, float& taup) {
+    const float c2 = h.c2;
     const float taup_m = with_margin(taup);
     const float tauq_m = HASQ ? with_margin(tauq) : 0.0f;
 
@@ -433,8 +443,8 @@ __device__ __forceinline__ void filter_tile(const RaceArgs& a, const Seg& c, Lds
     philox4x32_10((uint32_t)i0 >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, x);      // tokens i0 .. i0 + 3
     philox4x32_10((uint32_t)i1 >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, x + 4);  // tokens i1 .. i1 + 3
     float lp[8], lq[8];
-    unpack<RAWF32>(rp, lp);
-    if (HASQ) unpack<RAWF32>(rq, lq);
+    unpack<RAWF32>(rp, lp, h.sh16);
+    if (HASQ) unpack<RAWF32>(rq, lq, h.sh16);
 
     float accp = -INFINITY, accq = -INFINITY;
 #pragma unroll
@@ -447,23 +457,26 @@ __device__ __forceinline__ void filter_tile(const RaceArgs& a, const Seg& c, Lds
     if (HASQ) flag = flag || (accq >= tauq_m);
 
     if (__builtin_amdgcn_ballot_w64(flag) != 0)  // rare: some lane holds a token that may matter
-        refine_tile<RAWF32, HASQ>(lds, c2, i0, i1, c.end, rq, rp, x, flag, tauq_m, taup_m, tauq, taup);
+        refine_tile<RAWF32, HASQ>(lds, a.c2, i0, i1, c.end, rq, rp, x, flag, tauq_m, taup_m, tauq, taup);
 }
 
 // One lane's share of a tile: its two pieces.  A bf16 piece is 8 tokens and is filtered on its own; two fp32
 // pieces (or the 8 consecutive tokens of the element-load path) make one group of 8.
 template <int DT, bool VEC, bool HASQ>
-__device__ __forceinline__ void filter_lane(const RaceArgs& a, const Seg& c, Lds& lds, int32_t ia, int32_t ib,
-                                            const Raw& rq, const Raw& rp, float& tauq, float& taup) {
+__device__ __forceinline__ void filter_lane(const RaceArgs& a, const Seg& c, Lds& lds, const HotConsts& h, int32_t ia,
+                                            int32_t ib, const Raw& rq, const Raw& rp, float& tauq, float& taup) {
     constexpr bool RAWF32 = (DT == ERSD_F32) || !VEC;
+    // the workgroup's bound, possibly raised by another wavefront since the last tile
+    taup = fmaxf(taup, lds_tau(lds, 1));
+    if (HASQ) tauq = fmaxf(tauq, lds_tau(lds, 0));
     if (VEC && DT == ERSD_BF16) {
         Raw hq, hp;
         hq.a = rq.a; hq.b = rq.a; hp.a = rp.a; hp.b = rp.a;
-        filter_tile<RAWF32, HASQ>(a, c, lds, ia, ia + 4, hq, hp, tauq, taup);
+        filter_tile<RAWF32, HASQ>(a, c, lds, h, ia, ia + 4, hq, hp, tauq, taup);
         hq.a = rq.b; hq.b = rq.b; hp.a = rp.b; hp.b = rp.b;
-        filter_tile<RAWF32, HASQ>(a, c, lds, ib, ib + 4, hq, hp, tauq, taup);
+        filter_tile<RAWF32, HASQ>(a, c, lds, h, ib, ib + 4, hq, hp, tauq, taup);
     } else {
-        filter_tile<RAWF32, HASQ>(a, c, lds, ia, ib, rq, rp, tauq, taup);
+        filter_tile<RAWF32, HASQ>(a, c, lds, h, ia, ib, rq, rp, tauq, taup);
     }
 }
 
@@ -510,11 +523,12 @@ __device__ void filter_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
         taup = wave_max(taup);
         if (HASQ) tauq = wave_max(tauq);
         if ((tid & (kWave - 1)) == 0) {
-            atomicMax(&lds.tau[1], ordered_int(taup));
-            if (HASQ) atomicMax(&lds.tau[0], ordered_int(tauq));
+            lds_tau_raise(lds, 1, taup);
+            if (HASQ) lds_tau_raise(lds, 0, tauq);
         }
     }
 
+    const HotConsts h = make_hot_consts(a.c2);
     // kStages tiles per trip; buffer indices are compile-time constants, so the ring stays in registers
     for (int32_t base = c.begin; base < c.end; base += kStages * kTile) {
         bool done = false;
@@ -526,8 +540,8 @@ __device__ void filter_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
                 const int32_t nt = base + (st + kAhead) * kTile, ct = base + st * kTile;
                 pr[nb] = load_raw<DT, VEC>(c.prow, TS::piece_a(nt, tid), TS::piece_b(nt, tid), c.end);
                 if (HASQ) q[nb] = load_raw<DT, VEC>(c.qrow, TS::piece_a(nt, tid), TS::piece_b(nt, tid), c.end);
-                filter_lane<DT, VEC, HASQ>(a, c, lds, TS::piece_a(ct, tid), TS::piece_b(ct, tid), q[st], pr[st], tauq,
-                                           taup);
+                filter_lane<DT, VEC, HASQ>(a, c, lds, h, TS::piece_a(ct, tid), TS::piece_b(ct, tid), q[st], pr[st],
+                                           tauq, taup);
                 done = base + (st + 1) * kTile >= c.end;  // workgroup-uniform
             }
         }
@@ -544,7 +558,7 @@ template <int DT, bool VEC>
 __device__ void race_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
     const int tid = threadIdx.x;
     if (tid < 2) {
-        lds.tau[tid] = ordered_int(kTauInit);
+        lds.tau[tid] = kTauInit;
         lds.count[tid] = 0;
         lds.nsurv[tid] = 0;
     }
