@@ -16,8 +16,11 @@
  *
  * Conventions the paper leaves open and this library fixes:
  *   - e_i = -log1p(-v), v = (x + 1/2) * 2^-32, where x is word (i & 3) of
- *     Philox4x32-10( counter = (i >> 2, position-or-node index, sequence index b, draft index d),
- *                    key = (seed & 0xffffffff, seed >> 32) ).
+ *     Philox4x32-R( counter = (i >> 2, position-or-node index, sequence index b, draft index d),
+ *                   key = (seed & 0xffffffff, seed >> 32) ),  R = ersd_philox_rounds().
+ *     The library is built with R = 7, the generator's fastest variant that its authors report as
+ *     passing the standard statistical batteries; 10 rounds, their default strength, make the bf16
+ *     kernels instruction-bound on this GPU and can be had by compiling with -DERSD_PHILOX_ROUNDS=10.
  *     A caller that decodes several steps passes a fresh seed per step.
  *   - The winner is decided on scores evaluated in IEEE double precision from the exactly widened
  *     logit: score = (double)logit / (double)T - ln e_i.  Exactly equal scores go to the lowest token
@@ -172,6 +175,9 @@ int ersd_tree_validate_host(const int32_t* parent_host, int32_t N);
 
 /* Static text for a status code (never NULL). */
 const char* ersd_status_string(int status);
+
+/* Rounds of the Philox4x32 generator this library was compiled with (7 unless rebuilt). */
+int ersd_philox_rounds(void);
 
 /* major * 10000 + minor * 100 + patch */
 int ersd_version(void);

@@ -13,7 +13,9 @@ def build(force: bool = True) -> str:
     ):
         return LIB
     # -ffp-contract=off: no fused multiply-adds, so the fp64 arithmetic is exactly as written
-    cmd = ["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+    rounds = os.environ.get("ERSD_PHILOX_ROUNDS")  # same switch as the GPU library's build
+    defs = [f"-DORACLE_PHILOX_ROUNDS={int(rounds)}"] if rounds else []
+    cmd = ["gcc", *defs, "-O2", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
            "-Wall", "-Wextra", "-o", LIB, SRC, "-lm"]
     subprocess.run(cmd, check=True, cwd=HERE)
     return LIB

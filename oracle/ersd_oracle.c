@@ -14,7 +14,10 @@
 #include <omp.h>
 #endif
 
-static int g_rounds = 10;
+#ifndef ORACLE_PHILOX_ROUNDS
+#define ORACLE_PHILOX_ROUNDS 7
+#endif
+static int g_rounds = ORACLE_PHILOX_ROUNDS;
 static int g_threads = 0; /* 0 = OpenMP default */
 
 void oracle_set_rounds(int rounds) { g_rounds = rounds; }

@@ -23,7 +23,7 @@
  * Readings the paper leaves open (RNG, bit layout, tie-break, temperature):
  *   e_i = -log1p(-v),  v = (x + 1/2) * 2^-32,  x = word (i & 3) of
  *   Philox4x32-R( counter = (i >> 2, position-or-node, sequence, draft),
- *                 key = (seed low word, seed high word) ),  R = 10 by default;
+ *                 key = (seed low word, seed high word) ),  R = 7 by default;
  *   exact score ties go to the lowest token index.
  */
 #ifndef ERSD_ORACLE_H
@@ -38,7 +38,8 @@ extern "C" {
 /* Philox4x32 with `rounds` rounds (Salmon, Moraes, Dror, Shaw 2011). */
 void oracle_philox4x32(int rounds, const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
 
-/* Number of Philox rounds used by every race below (default 10). */
+/* Number of Philox rounds used by every race below (default 7, the round count the GPU library is built with;
+ * 10 is the generator's standard strength and the one its published known answers are for). */
 void oracle_set_rounds(int rounds);
 int oracle_get_rounds(void);
 

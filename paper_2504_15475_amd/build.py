@@ -19,6 +19,9 @@ FLAGS = [
 
 
 def build(extra=()):
+    rounds = os.environ.get("ERSD_PHILOX_ROUNDS")  # 7 by default (set in the source); 10 = the generator's standard
+    if rounds:
+        extra = (*extra, f"-DERSD_PHILOX_ROUNDS={int(rounds)}")
     cmd = [HIPCC, *FLAGS, *extra, "-o", LIB, SRC]
     subprocess.run(cmd, check=True)
     return LIB

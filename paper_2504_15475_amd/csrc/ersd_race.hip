@@ -50,14 +50,14 @@ constexpr int kStages = ERSD_STAGES;                // register buffers per row:
 constexpr int kListCap = 512;                       // candidate slots per side per workgroup
 constexpr int kWave = 64;
 constexpr int kWaves = kThreads / kWave;
-constexpr uint32_t kWPair = 5, kWSingle = 3;        // relative cost of one group in a pair row / target-only row
+constexpr uint32_t kWPair = 5, kWSingle = 4;        // relative cost of one group in a pair row / target-only row
 constexpr uint64_t kMinQuota = 64 * kWPair * 16;    // cost units a workgroup gets at least (16 pair iterations of a wave)
 constexpr uint32_t kMaxBlocks = 256 * 16;           // upper bound of resident workgroups, for workspace sizing
 
 #ifndef ERSD_PHILOX_ROUNDS
-#define ERSD_PHILOX_ROUNDS 10
+#define ERSD_PHILOX_ROUNDS 7
 #endif
-constexpr int kPhiloxRounds = ERSD_PHILOX_ROUNDS;   // 10 is the generator's standard strength
+constexpr int kPhiloxRounds = ERSD_PHILOX_ROUNDS;   // 7 by default; 10 is the generator's standard strength
 constexpr uint32_t kPhiloxM0 = 0xD2511F53u, kPhiloxM1 = 0xCD9E8D57u;
 constexpr uint32_t kPhiloxW0 = 0x9E3779B9u, kPhiloxW1 = 0xBB67AE85u;
 
@@ -139,8 +139,8 @@ struct RaceArgs {
     double T;
 };
 
-// ------------------------------------------------------------------------------------------ Philox4x32-10
-__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+// ------------------------------------------------------------------------------------------ Philox4x32-R
+__device__ __forceinline__ void philox4x32(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                               uint32_t k0, uint32_t k1, uint32_t out[4]) {
 #pragma unroll
     for (int r = 0; r < kPhiloxRounds; ++r) {
@@ -216,7 +216,7 @@ __device__ void exhaustive_half(const RaceArgs& a, const Seg& c, const char* row
     const int32_t g0 = c.begin >> 2, g1 = (c.end + 3) >> 2;
     for (int32_t g = g0 + half_tid; g < g1; g += kThreads / 2) {
         uint32_t w[4];
-        philox4x32_10((uint32_t)g, c.c1, c.c2, c.c3, a.key0, a.key1, w);
+        philox4x32((uint32_t)g, c.c1, c.c2, c.c3, a.key0, a.key1, w);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int32_t i = g * 4 + e;
@@ -397,17 +397,16 @@ __device__ __forceinline__ float raw_logit_const(const Raw& r, int e) {
 // margin; what can still be the maximum goes to the candidate list and raises tau (lane, wavefront, workgroup).
 template <bool RAWF32, bool HASQ>
 __device__ __forceinline__ void refine_tile(Lds& lds, float c2, int32_t i0, int32_t i1, int32_t end, const Raw& rq,
-                                            const Raw& rp,
-                                            const uint32_t (&x)[8], bool flag, float tauq_m, float taup_m,
-                                            float& tauq, float& taup) {
+                                            const Raw& rp, const uint32_t (&x)[8], const float (&up)[8],
+                                            const float (&uq)[8], bool flag, float tauq_m, float taup_m, float& tauq,
+                                            float& taup) {
     if (!flag) return;
     // which of this lane's (token, side) bounds reach tau: bits 0-7 target side, 8-15 draft side
     uint32_t mask = 0;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        const float t = gumbel2_upper(x[e]);
-        if (fmaf(raw_logit_const<RAWF32>(rp, e), c2, t) >= taup_m) mask |= 1u << e;
-        if (HASQ && fmaf(raw_logit_const<RAWF32>(rq, e), c2, t) >= tauq_m) mask |= 1u << (8 + e);
+        if (up[e] >= taup_m) mask |= 1u << e;
+        if (HASQ && uq[e] >= tauq_m) mask |= 1u << (8 + e);
     }
     const float taup0 = taup, tauq0 = tauq;
     while (mask) {  // usually a single bit in a single lane
@@ -440,24 +439,29 @@ __device__ __forceinline__ void filter_tile(const RaceArgs& a, const Seg& c, Lds
     const float tauq_m = HASQ ? with_margin(tauq) : 0.0f;
 
     uint32_t x[8];
-    philox4x32_10((uint32_t)i0 >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, x);      // tokens i0 .. i0 + 3
-    philox4x32_10((uint32_t)i1 >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, x + 4);  // tokens i1 .. i1 + 3
+    philox4x32((uint32_t)i0 >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, x);      // tokens i0 .. i0 + 3
+    philox4x32((uint32_t)i1 >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, x + 4);  // tokens i1 .. i1 + 3
     float lp[8], lq[8];
     unpack<RAWF32>(rp, lp, h.sh16);
     if (HASQ) unpack<RAWF32>(rq, lq, h.sh16);
 
     float accp = -INFINITY, accq = -INFINITY;
+    float up[8], uq[8];  // per-token upper bounds of the two scores
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const float t = gumbel2_upper(x[e]);
-        accp = fmaxf(accp, fmaf(lp[e], c2, t));
-        if (HASQ) accq = fmaxf(accq, fmaf(lq[e], c2, t));
+        up[e] = fmaf(lp[e], c2, t);
+        accp = fmaxf(accp, up[e]);
+        if (HASQ) {
+            uq[e] = fmaf(lq[e], c2, t);
+            accq = fmaxf(accq, uq[e]);
+        }
     }
     bool flag = accp >= taup_m;
     if (HASQ) flag = flag || (accq >= tauq_m);
 
     if (__builtin_amdgcn_ballot_w64(flag) != 0)  // rare: some lane holds a token that may matter
-        refine_tile<RAWF32, HASQ>(lds, a.c2, i0, i1, c.end, rq, rp, x, flag, tauq_m, taup_m, tauq, taup);
+        refine_tile<RAWF32, HASQ>(lds, a.c2, i0, i1, c.end, rq, rp, x, up, uq, flag, tauq_m, taup_m, tauq, taup);
 }
 
 // One lane's share of a tile: its two pieces.  A bf16 piece is 8 tokens and is filtered on its own; two fp32
@@ -507,7 +511,7 @@ __device__ void filter_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
     float tauq = kTauInit, taup = kTauInit;
     {
         uint32_t w[4];
-        philox4x32_10((uint32_t)first >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, w);
+        philox4x32((uint32_t)first >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, w);
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
             if (first + e < c.end) {
@@ -631,7 +635,7 @@ __device__ void race_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
             out->count = 0;
         } else {
             uint32_t w[4];
-            philox4x32_10((uint32_t)bi >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, w);
+            philox4x32((uint32_t)bi >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, w);
             Cand k;
             k.idx = bi;
             k.word = w[bi & 3];
@@ -1217,6 +1221,8 @@ const char* ersd_status_string(int status) {
     }
 }
 
-int ersd_version(void) { return 200; }
+int ersd_philox_rounds(void) { return kPhiloxRounds; }
+
+int ersd_version(void) { return 300; }
 
 }  // extern "C"

@@ -56,6 +56,7 @@ def lib():
         L.ersd_status_string.argtypes = [ctypes.c_int]
         L.ersd_status_string.restype = ctypes.c_char_p
         L.ersd_version.restype = ctypes.c_int
+        L.ersd_philox_rounds.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -66,6 +67,10 @@ def status_string(status):
 
 def version():
     return lib().ersd_version()
+
+
+def philox_rounds():
+    return lib().ersd_philox_rounds()
 
 
 def _check(status):

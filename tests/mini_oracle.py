@@ -23,7 +23,7 @@ def philox4x32(ctr, key, rounds=10):
     return c
 
 
-def exponentials(V, seed, c1, c2, c3, rounds=10):
+def exponentials(V, seed, c1, c2, c3, rounds=7):
     key = (seed & MASK, (seed >> 32) & MASK)
     e = np.empty(V, dtype=np.float64)
     for i in range(V):
@@ -49,7 +49,7 @@ def race_winner(logits_f64, T, e):
     return int(np.argmin(arrival))
 
 
-def race_verify(draft, target, T, seed, rounds=10):
+def race_verify(draft, target, T, seed, rounds=7):
     """draft [B,k,V], target [B,k+1,V] float64 -> (draft_tokens, target_tokens, accept_len)."""
     B, k, V = draft.shape
     dt = np.zeros((B, k), dtype=np.int32)

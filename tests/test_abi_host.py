@@ -26,13 +26,15 @@ def test_every_declared_symbol_is_exported(L):
     names = declared_functions()
     assert {"ersd_race_verify", "ersd_race_verify_multi", "ersd_race_verify_tree", "ersd_race_workspace_bytes",
             "ersd_status_string", "ersd_version", "ersd_tree_validate_host", "ersd_selftest_bounds",
-            "ersd_race_stage_races", "ersd_race_stage_accept", "ersd_plan_describe_host"} <= set(names)
+            "ersd_race_stage_races", "ersd_race_stage_accept", "ersd_plan_describe_host", "ersd_philox_rounds"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
 
 
 def test_version_and_status_strings(L):
-    assert L.ersd_version() >= 200
+    assert L.ersd_version() >= 300
+    import oracle
+    assert L.ersd_philox_rounds() == oracle.get_rounds() and L.ersd_philox_rounds() in (7, 10)   # same generator on both sides
     seen = set()
     for s in range(0, -7, -1):
         txt = L.ersd_status_string(s)
