@@ -50,8 +50,12 @@ constexpr int kStages = ERSD_STAGES;                // register buffers per row:
 constexpr int kListCap = 512;                       // candidate slots per side per workgroup
 constexpr int kWave = 64;
 constexpr int kWaves = kThreads / kWave;
-constexpr uint32_t kWPair = 5, kWSingle = 4;        // relative cost of one group in a pair row / target-only row
-constexpr uint64_t kMinQuota = 64 * kWPair * 16;    // cost units a workgroup gets at least (16 pair iterations of a wave)
+#ifndef ERSD_W_PAIR
+#define ERSD_W_PAIR 10
+#define ERSD_W_SINGLE 7
+#endif
+constexpr uint32_t kWPair = ERSD_W_PAIR, kWSingle = ERSD_W_SINGLE;  // relative cost of one group in a pair row / target-only row
+constexpr uint64_t kMinQuota = 64 * kWPair * 16;     // cost units a workgroup gets at least (16 pair iterations of a wave)
 constexpr uint32_t kMaxBlocks = 256 * 16;           // upper bound of resident workgroups, for workspace sizing
 
 #ifndef ERSD_PHILOX_ROUNDS
@@ -715,11 +719,16 @@ struct FinishArgs {
 // work on one row side, each taking every eighth segment slot; every lane of the wavefront must call this
 // (`active` false for lanes without work) because the lanes of a group meet in shuffles.
 __device__ int32_t resolve_row(const SegOut* o, uint32_t nslots, double T, bool active, int lane8) {
+    // a row rarely has more than eight segments: each lane reads its first slot once and keeps it in registers
+    SegOut mine;
+    mine.count = 0;
+    const bool have = active && (uint32_t)lane8 < nslots;
+    if (have) mine = o[lane8];
     float lstar = -INFINITY;
     int32_t total = 0;
-    if (active)
+    if (have)
         for (uint32_t s = lane8; s < nslots; s += 8) {
-            const SegOut so = o[s];
+            const SegOut so = s == (uint32_t)lane8 ? mine : o[s];
 #pragma unroll
             for (int32_t k = 0; k < kMaxSurvivors; ++k)
                 if (k < so.count) {
@@ -733,9 +742,9 @@ __device__ int32_t resolve_row(const SegOut* o, uint32_t nslots, double T, bool 
         total += __shfl_xor(total, off, 8);
     }
     int32_t contenders = 0, only = -1;
-    if (active && total > 0)
+    if (have && total > 0)
         for (uint32_t s = lane8; s < nslots; s += 8) {
-            const SegOut so = o[s];
+            const SegOut so = s == (uint32_t)lane8 ? mine : o[s];
 #pragma unroll
             for (int32_t k = 0; k < kMaxSurvivors; ++k)
                 if (k < so.count && so.c[k].s2 + refine_err(so.c[k].s2) >= lstar) {
@@ -749,11 +758,12 @@ __device__ int32_t resolve_row(const SegOut* o, uint32_t nslots, double T, bool 
         only = max(only, __shfl_xor(only, off, 8));
     }
     if (total == 0) return 0;  // every score of the row is -inf: lowest index
+    if (contenders == 1) return only;  // uniform over the eight lanes
     double bs = -INFINITY;
     int32_t bi = -1;
-    if (contenders > 1 && active)  // fp32 cannot tell: score the contenders exactly
+    if (have)  // fp32 cannot tell: score the contenders exactly
         for (uint32_t s = lane8; s < nslots; s += 8) {
-            const SegOut so = o[s];
+            const SegOut so = s == (uint32_t)lane8 ? mine : o[s];
             for (int32_t k = 0; k < so.count; ++k) {
                 const Cand cd = so.c[k];
                 if (cd.s2 + refine_err(cd.s2) >= lstar) {
@@ -768,7 +778,7 @@ __device__ int32_t resolve_row(const SegOut* o, uint32_t nslots, double T, bool 
         const int32_t oi = __shfl_xor(bi, off, 8);
         if (oi >= 0 && (bi < 0 || better(os, oi, bs, bi))) { bs = os; bi = oi; }
     }
-    return contenders > 1 ? bi : only;
+    return bi;
 }
 
 // Tokens: every (row, side) pair is resolved by eight lanes; 32 pairs per workgroup.
