@@ -34,6 +34,9 @@ def main():
     ap.add_argument("--buffers", type=int, default=4, help="distinct input sets rotated through (cache defeat)")
     ap.add_argument("--event-every", type=int, default=8,
                     help="record HIP events around the race kernel of every N-th timed step (events cost a few us)")
+    ap.add_argument("--entry", choices=["verify", "sample"], default="verify",
+                    help="verify: the fused draft+target races (default, the headline metric); sample: the one-model "
+                         "entry point on the workload's target logits (how a serving loop calls the race)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fused-call", action="store_true",
                     help="issue each step through the single verify entry point (no event between the stages)")
@@ -52,6 +55,9 @@ def main():
     variant = {"sequence": race.VARIANT_SEQUENCE, "multi": race.VARIANT_MULTI, "tree": race.VARIANT_TREE}[w.variant]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.entry == "sample":
+        return bench_sample(args, w, dev)
 
     base = wl.make_inputs(w, dev)
     sets = [base]
@@ -127,6 +133,47 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"], out["check"] = cpu_baseline(w, base, calls[0], variant)
     print(json.dumps(out), flush=True)
+    return 0
+
+
+def bench_sample(args, w, dev):
+    """One-model races (ersd_race_sample) on the workload's target logits; events bracket the whole call."""
+    from paper_2504_15475_amd import race, workloads as wl
+    base = wl.make_inputs(w, dev)["target"]
+    if w.variant != "multi":
+        base = base.unsqueeze(1)
+    base = base.contiguous()
+    sets = [base] + [(base.float() + 0.01 * torch.randn(base.shape, device=dev)).to(base.dtype).contiguous()
+                     for _ in range(max(1, args.buffers) - 1)]
+    B, m, npos, V = base.shape
+    need = int(race.lib().ersd_race_sample_workspace_bytes(B, m, npos, V, race._dtype_code(base)))
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    for i in range(args.warmup):
+        race.race_sample(sets[i % len(sets)], 0, w.temperature, w.seed, workspace=ws)
+    torch.cuda.synchronize()
+    K = args.steps
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(K):
+        race.race_sample(sets[i % len(sets)], 0, w.temperature, w.seed, workspace=ws)
+    e1.record()
+    torch.cuda.synchronize()
+    total_s = time.perf_counter() - t0
+    elements = base.numel()
+    gpu_ms = e0.elapsed_time(e1) / K
+    nbytes = elements * base.element_size()
+    print(json.dumps({
+        "metric": "race_elements_per_sec", "value": elements * K / total_s, "unit": "elements/s", "n_gpus": 1,
+        "steps": K, "warmup": args.warmup, "ms_per_step": total_s * 1e3 / K, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": w.name + ":target rows only", "entry": "ersd_race_sample", "rows": B * m * npos, "V": V,
+                   "philox_rounds": race.philox_rounds()},
+        "roofline": {"bound": "hbm", "achieved": round(nbytes / (gpu_ms * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": round(nbytes / (gpu_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4), "traffic": None,
+                     "kernel": "race_kernel + resolve_kernel (whole call)", "kernel_ms_avg": round(gpu_ms, 5),
+                     "algorithmic_bytes_per_launch": nbytes},
+    }), flush=True)
     return 0
 
 

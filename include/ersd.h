@@ -161,6 +161,32 @@ int ersd_plan_describe_host(int variant, int32_t B, int32_t m, int32_t k_or_N, i
                             uint32_t* row_first, uint32_t* row_last);
 
 /*
+ * The race of ONE model's logits, for callers that draft and verify at different times (the order of
+ * Algorithm 2: the draft model's race picks the drafted token, the target model is evaluated on it, and
+ * only then is the same race run under the target model).  Because the exponentials are a function of
+ * (seed, sequence, draft, position, token) alone, racing the draft rows and the target rows in separate
+ * calls gives exactly the tokens of the fused verify calls.
+ *   logits [B, m, npos, V]: rows of one model at positions pos0 .. pos0 + npos - 1 of every sequence
+ *   tokens [B, m, npos] out: race winner of row (b, d, j), counter words (i >> 2, pos0 + j, b, d)
+ * A drafting loop calls it with npos = 1 and pos0 = the step; verification calls it on the target
+ * logits with pos0 = 0, npos = k + 1 (sequence, multi) or npos = N (tree: positions are node indices).
+ * Workspace size: ersd_race_sample_workspace_bytes.  Same memory, stream and error rules as above.
+ */
+int ersd_race_sample(const void* logits, ersd_dtype dt, int32_t B, int32_t m, int32_t npos, int32_t V,
+                     int32_t pos0, float temperature, uint64_t seed, int32_t* tokens,
+                     void* workspace, size_t workspace_bytes, void* stream);
+size_t ersd_race_sample_workspace_bytes(int32_t B, int32_t m, int32_t npos, int32_t V, ersd_dtype dt);
+
+/*
+ * The acceptance step alone, on tokens the caller already holds (device arrays laid out as in the verify
+ * call of the same `variant`): first disagreement per draft (Section 2), best draft, or the tree walk.
+ * Outputs the variant does not have are ignored and may be NULL.
+ */
+int ersd_accept_lengths(int variant, int32_t B, int32_t m, int32_t k_or_N, const int32_t* parent,
+                        const int32_t* draft_tokens, const int32_t* target_tokens, int32_t* accept_len,
+                        int32_t* best_draft, int32_t* best_len, int32_t* accept_node, void* stream);
+
+/*
  * Device self-check of the two single-precision bounds the streaming filter relies on, over all 2^32
  * generator words, against double precision.  counters: DEVICE array of 4 uint64, written as
  *   [0] words whose cheap upper bound of -log2 e fell below the true value      (must be 0)

@@ -57,6 +57,8 @@ def lib():
         L.oracle_race_rows.restype = None
         L.oracle_row_candidates.argtypes = [vp, ctypes.c_int, i64, f32, u64, u32, u32, u32, ctypes.c_double, vp, i64]
         L.oracle_row_candidates.restype = i64
+        L.oracle_race_sample.argtypes = [vp, ctypes.c_int, i32, i32, i32, i64, i32, f32, u64, vp, vp]
+        L.oracle_race_sample.restype = ctypes.c_int
         L.oracle_race_verify.argtypes = [vp, vp, ctypes.c_int, i32, i32, i64, f32, u64, vp, vp, vp, vp, vp]
         L.oracle_race_verify.restype = ctypes.c_int
         L.oracle_race_verify_multi.argtypes = [vp, vp, ctypes.c_int, i32, i32, i32, i64, f32, u64,
@@ -156,6 +158,19 @@ def row_candidates(row, temperature, seed, c1=0, c2=0, c3=0, tol_rel=1e-6, cap=4
     n = lib().oracle_row_candidates(_ptr(a), d, a.shape[0], float(temperature), int(seed), int(c1), int(c2), int(c3),
                                     float(tol_rel), _ptr(out), cap)
     return out[: min(n, cap)], n
+
+
+def race_sample(logits, pos0, temperature, seed, want_info=False):
+    """One model's races.  logits [B,m,npos,V] -> tokens [B,m,npos] (and the row records)."""
+    a, dt = _host(logits)
+    B, m, npos, V = a.shape
+    tok = np.zeros((B, m, npos), dtype=np.int32)
+    info = np.zeros((B, m, npos), dtype=ROW_INFO_DTYPE) if want_info else None
+    rc = lib().oracle_race_sample(_ptr(a), dt, B, m, npos, V, int(pos0), float(temperature), int(seed), _ptr(tok),
+                                  _ptr(info) if want_info else None)
+    if rc != 0:
+        raise ValueError("oracle_race_sample: invalid arguments")
+    return (tok, info) if want_info else tok
 
 
 def race_verify(draft, target, temperature, seed, want_info=False):

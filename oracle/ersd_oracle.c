@@ -225,6 +225,27 @@ int oracle_race_verify_multi(const void* draft, const void* target, int dtype,
     return 0;
 }
 
+int oracle_race_sample(const void* logits, int dtype, int32_t B, int32_t m, int32_t npos, int64_t V, int32_t pos0,
+                       float temperature, uint64_t seed, int32_t* tokens, oracle_row_info* info) {
+    if (bad_common(logits, logits, dtype, V, temperature)) return -1;
+    if (B < 1 || m < 1 || npos < 1 || pos0 < 0 || !tokens) return -1;
+    const size_t es = elem_size(dtype);
+    const int64_t nrace = (int64_t)B * m * npos;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t r = 0; r < nrace; ++r) {
+        const int32_t j = (int32_t)(r % npos);
+        const int32_t d = (int32_t)((r / npos) % m);
+        const int32_t b = (int32_t)(r / ((int64_t)npos * m));
+        /* a one-model race: the same counters as the two-model race at that (sequence, draft, position) */
+        const void* rows[2] = {NULL, (const char*)logits + (size_t)(r * V) * es};
+        oracle_row_info out[2];
+        oracle_race_rows(rows, dtype, V, temperature, seed, (uint32_t)(pos0 + j), (uint32_t)b, (uint32_t)d, out);
+        tokens[r] = out[1].token;
+        if (info) info[r] = out[1];
+    }
+    return 0;
+}
+
 int oracle_race_verify(const void* draft, const void* target, int dtype,
                        int32_t B, int32_t k, int64_t V, float temperature, uint64_t seed,
                        int32_t* draft_tokens, int32_t* target_tokens, int32_t* accept_len,

@@ -72,6 +72,14 @@ int64_t oracle_row_candidates(const void* row, int dtype, int64_t V, float tempe
                               double tol_rel, int32_t* out_idx, int64_t cap);
 
 /*
+ * One model's races: logits [B,m,npos,V] at positions pos0 .. pos0+npos-1, tokens [B,m,npos]; race (b,d,j)
+ * uses counter words (i >> 2, pos0 + j, b, d), i.e. the exponentials of the two-model race at that place
+ * (Algorithm 2 runs the draft race first and the target race, on the same e, after the target evaluation).
+ */
+int oracle_race_sample(const void* logits, int dtype, int32_t B, int32_t m, int32_t npos, int64_t V, int32_t pos0,
+                       float temperature, uint64_t seed, int32_t* tokens, oracle_row_info* info);
+
+/*
  * Sequence variant.  draft [B,k,V], target [B,k+1,V].
  * draft_tokens [B,k], target_tokens [B,k+1], accept_len [B];
  * draft_info [B,k] and target_info [B,k+1] may be NULL.

@@ -137,6 +137,7 @@ struct RaceArgs {
     Part part;
     int32_t V;
     int32_t m;          // drafts per prompt
+    uint32_t pos0;      // position index of a sequence's first row (counter word 1 = pos0 + j)
     uint32_t key0, key1;
     float c2;           // log2(e) / T
     int32_t exhaustive; // score every token in fp64 (reference path for tests)
@@ -678,7 +679,7 @@ race_kernel(RaceArgs a) {
         const uint32_t g1 = left < (uint64_t)(p.V8 - g0) ? g0 + (uint32_t)left : p.V8;
         c.prow = a.target + (size_t)row * (size_t)a.V * es;
         c.qrow = j < p.kd ? a.draft + (size_t)(seq * p.kd + j) * (size_t)a.V * es : nullptr;
-        c.c1 = j;
+        c.c1 = a.pos0 + j;
         c.c2 = prompt;
         c.c3 = d;
         c.begin = (int32_t)(g0 * 8);
@@ -1030,7 +1031,7 @@ int plan_part(const Geometry& g, ersd_dtype dt, size_t ws_bytes, Part& p) {
 }
 
 int launch_races(const void* dl, const void* tl, ersd_dtype dt, const Geometry& g, float T, uint64_t seed, void* ws,
-                 size_t ws_bytes, void* stream) {
+                 size_t ws_bytes, void* stream, uint32_t pos0 = 0) {
     RaceArgs a;
     const int rc = plan_part(g, dt, ws_bytes, a.part);
     if (rc != ERSD_OK) return rc;
@@ -1039,6 +1040,7 @@ int launch_races(const void* dl, const void* tl, ersd_dtype dt, const Geometry& 
     a.out = static_cast<SegOut*>(ws);
     a.V = g.V;
     a.m = g.m;
+    a.pos0 = pos0;
     a.key0 = (uint32_t)(seed & 0xffffffffu);
     a.key1 = (uint32_t)(seed >> 32);
     a.T = (double)T;
@@ -1079,7 +1081,10 @@ int launch_finish(int variant, const Geometry& g, ersd_dtype dt, float T, const 
     f.accept_node = accept_node;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint64_t items = f.part.rows * 2;
-    if ((uint64_t)g.m * g.kt * 2 <= 2 * (kThreads / 8)) {  // at most two passes per prompt: one launch
+    if (variant < 0) {  // tokens only
+        hipLaunchKernelGGL(resolve_kernel, dim3((uint32_t)((items + kThreads / 8 - 1) / (kThreads / 8))),
+                           dim3(kThreads), 0, s, f);
+    } else if ((uint64_t)g.m * g.kt * 2 <= 2 * (kThreads / 8)) {  // at most two passes per prompt: one launch
         hipLaunchKernelGGL(finish_kernel, dim3((uint32_t)g.B), dim3(kThreads), 0, s, f);
     } else {
         hipLaunchKernelGGL(resolve_kernel, dim3((uint32_t)((items + kThreads / 8 - 1) / (kThreads / 8))),
@@ -1180,6 +1185,57 @@ int ersd_race_verify_tree(const void* draft_logits, const void* target_logits, e
     if (workspace_bytes < workspace_for(g)) return ERSD_ERR_WORKSPACE_TOO_SMALL;
     return launch(draft_logits, target_logits, dt, g, temperature, seed, ERSD_VARIANT_TREE, parent, draft_tokens,
                   target_tokens, accept_len, nullptr, nullptr, accept_node, workspace, workspace_bytes, stream);
+}
+
+int ersd_race_sample(const void* logits, ersd_dtype dt, int32_t B, int32_t m, int32_t npos, int32_t V, int32_t pos0,
+                     float temperature, uint64_t seed, int32_t* tokens, void* workspace, size_t workspace_bytes,
+                     void* stream) {
+    if (!tokens || !workspace) return ERSD_ERR_NULL_POINTER;
+    const int rc = check_common(logits, logits, dt, temperature, workspace);
+    if (rc != ERSD_OK) return rc;
+    Geometry g;
+    g.B = B; g.m = m; g.kd = 0; g.kt = npos; g.V = V;  // every row is raced on its own
+    if (npos < 1 || pos0 < 0 || (int64_t)pos0 + npos > 0x7fffffff || !sizes_ok(B, m, 1, npos, V))
+        return ERSD_ERR_INVALID_ARG;
+    if (workspace_bytes < workspace_for(g)) return ERSD_ERR_WORKSPACE_TOO_SMALL;
+    const int rr = launch_races(nullptr, logits, dt, g, temperature, seed, workspace, workspace_bytes, stream,
+                                (uint32_t)pos0);
+    if (rr != ERSD_OK) return rr;
+    return launch_finish(-1, g, dt, temperature, nullptr, nullptr, tokens, nullptr, nullptr, nullptr, nullptr,
+                         workspace, workspace_bytes, stream);
+}
+
+size_t ersd_race_sample_workspace_bytes(int32_t B, int32_t m, int32_t npos, int32_t V, ersd_dtype dt) {
+    if (dt != ERSD_F32 && dt != ERSD_BF16) return 0;
+    if (npos < 1 || !sizes_ok(B, m, 1, npos, V)) return 0;
+    Geometry g;
+    g.B = B; g.m = m; g.kd = 0; g.kt = npos; g.V = V;
+    return workspace_for(g);
+}
+
+int ersd_accept_lengths(int variant, int32_t B, int32_t m, int32_t k_or_N, const int32_t* parent,
+                        const int32_t* draft_tokens, const int32_t* target_tokens, int32_t* accept_len,
+                        int32_t* best_draft, int32_t* best_len, int32_t* accept_node, void* stream) {
+    if (!draft_tokens || !target_tokens || !accept_len) return ERSD_ERR_NULL_POINTER;
+    if (variant == ERSD_VARIANT_TREE && !parent) return ERSD_ERR_NULL_POINTER;
+    if (variant == ERSD_VARIANT_MULTI && (!best_draft || !best_len)) return ERSD_ERR_NULL_POINTER;
+    Geometry g;
+    if (!geometry(variant, B, m, k_or_N, 8, g)) return ERSD_ERR_INVALID_ARG;  // the vocabulary size plays no role
+    FinishArgs f;
+    f.part = make_part(g, 1);
+    f.out = nullptr;
+    f.T = 1.0;
+    f.m = g.m;
+    f.variant = variant;
+    f.parent = variant == ERSD_VARIANT_TREE ? parent : nullptr;
+    f.draft_tokens = const_cast<int32_t*>(draft_tokens);   // read only by accept_kernel
+    f.target_tokens = const_cast<int32_t*>(target_tokens);
+    f.accept_len = accept_len;
+    f.best_draft = variant == ERSD_VARIANT_MULTI ? best_draft : nullptr;
+    f.best_len = variant == ERSD_VARIANT_MULTI ? best_len : nullptr;
+    f.accept_node = variant == ERSD_VARIANT_TREE ? accept_node : nullptr;
+    hipLaunchKernelGGL(accept_kernel, dim3((uint32_t)g.B), dim3(kThreads), 0, static_cast<hipStream_t>(stream), f);
+    return hipGetLastError() == hipSuccess ? ERSD_OK : ERSD_ERR_HIP;
 }
 
 int ersd_selftest_bounds(uint64_t* counters, void* stream) {

@@ -49,6 +49,12 @@ def lib():
         L.ersd_plan_describe_host.argtypes = [ctypes.c_int, i32, i32, i32, i32, ctypes.c_uint32, vp, vp, vp, vp, vp]
         L.ersd_plan_describe_host.restype = ctypes.c_int
         L.ersd_race_stage_accept.restype = ctypes.c_int
+        L.ersd_race_sample.argtypes = [vp, ctypes.c_int, i32, i32, i32, i32, i32, f32, u64, vp, vp, sz, vp]
+        L.ersd_race_sample.restype = ctypes.c_int
+        L.ersd_race_sample_workspace_bytes.argtypes = [i32, i32, i32, i32, ctypes.c_int]
+        L.ersd_race_sample_workspace_bytes.restype = sz
+        L.ersd_accept_lengths.argtypes = [ctypes.c_int, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.ersd_accept_lengths.restype = ctypes.c_int
         L.ersd_selftest_bounds.argtypes = [vp, vp]
         L.ersd_selftest_bounds.restype = ctypes.c_int
         L.ersd_tree_validate_host.argtypes = [vp, i32]
@@ -173,6 +179,49 @@ def race_verify_tree(draft_logits, target_logits, parent, temperature, seed, wor
                                        int(seed), dtok.data_ptr(), ttok.data_ptr(), acc.data_ptr(), node.data_ptr(),
                                        ws.data_ptr(), ws_bytes, _stream()))
     return dtok, ttok, acc, node
+
+
+def race_sample(logits, pos0, temperature, seed, workspace=None):
+    """One model's races.  logits [B,m,npos,V] on the GPU -> tokens [B,m,npos]; race (b,d,j) is the race of
+    position pos0 + j (the drafting step, or 0 when a whole target tensor is raced)."""
+    x = _dev(logits, "logits")
+    code = _dtype_code(x)
+    B, m, npos, V = x.shape
+    need = int(lib().ersd_race_sample_workspace_bytes(B, m, npos, V, code))
+    if need == 0:
+        raise ErsdError(-2, status_string(-2))
+    ws = workspace if workspace is not None else torch.empty(need, dtype=torch.uint8, device=x.device)
+    tok = torch.empty((B, m, npos), dtype=torch.int32, device=x.device)
+    _check(lib().ersd_race_sample(x.data_ptr(), code, B, m, npos, V, int(pos0), float(temperature), int(seed),
+                                  tok.data_ptr(), ws.data_ptr(), ws.numel() * ws.element_size(), _stream()))
+    return tok
+
+
+def accept_lengths(variant, draft_tokens, target_tokens, parent=None):
+    """The acceptance step on token tensors laid out as the verify call of `variant` returns them."""
+    d, t = _dev(draft_tokens, "draft_tokens"), _dev(target_tokens, "target_tokens")
+    dev = d.device
+    i32 = dict(dtype=torch.int32, device=dev)
+    p = lambda x: None if x is None else x.data_ptr()
+    bd = bl = node = None
+    if variant == VARIANT_SEQUENCE:
+        B, k = d.shape
+        m, kn, acc = 1, k, torch.empty((B,), **i32)
+    elif variant == VARIANT_MULTI:
+        B, m, k = d.shape
+        kn, acc = k, torch.empty((B, m), **i32)
+        bd, bl = torch.empty((B,), **i32), torch.empty((B,), **i32)
+    else:
+        B, N = d.shape
+        m, kn, acc, node = 1, N, torch.empty((B,), **i32), torch.empty((B,), **i32)
+        _dev(parent, "parent")
+    _check(lib().ersd_accept_lengths(variant, B, m, kn, p(parent), d.data_ptr(), t.data_ptr(), acc.data_ptr(), p(bd),
+                                     p(bl), p(node), _stream()))
+    if variant == VARIANT_SEQUENCE:
+        return acc
+    if variant == VARIANT_MULTI:
+        return acc, bd, bl
+    return acc, node
 
 
 class PreparedVerify:

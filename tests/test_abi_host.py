@@ -26,7 +26,8 @@ def test_every_declared_symbol_is_exported(L):
     names = declared_functions()
     assert {"ersd_race_verify", "ersd_race_verify_multi", "ersd_race_verify_tree", "ersd_race_workspace_bytes",
             "ersd_status_string", "ersd_version", "ersd_tree_validate_host", "ersd_selftest_bounds",
-            "ersd_race_stage_races", "ersd_race_stage_accept", "ersd_plan_describe_host", "ersd_philox_rounds"} <= set(names)
+            "ersd_race_stage_races", "ersd_race_stage_accept", "ersd_plan_describe_host", "ersd_philox_rounds", "ersd_race_sample",
+            "ersd_race_sample_workspace_bytes", "ersd_accept_lengths"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
 
@@ -95,6 +96,25 @@ def test_multi_and_tree_argument_errors(L):
     assert L.ersd_race_stage_accept(1, 0, 1, 1, 2, 64, 1.0, None, FAKE, FAKE, FAKE, None, None, None, FAKE, 1 << 30, None) == -1
     assert L.ersd_race_stage_accept(0, 9, 1, 1, 2, 64, 1.0, None, FAKE, FAKE, FAKE, None, None, None, FAKE, 1 << 30, None) == -3
     assert L.ersd_race_stage_accept(0, 0, 1, 1, 2, 64, 0.0, None, FAKE, FAKE, FAKE, None, None, None, FAKE, 1 << 30, None) == -2
+
+
+def test_sample_and_accept_argument_errors(L):
+    def sample(**kw):
+        a = dict(x=FAKE, dt=1, B=2, m=1, npos=3, V=64, pos0=0, T=1.0, seed=0, tok=FAKE, ws=FAKE, wsb=1 << 30)
+        a.update(kw)
+        return L.ersd_race_sample(a["x"], a["dt"], a["B"], a["m"], a["npos"], a["V"], a["pos0"], a["T"], a["seed"],
+                                  a["tok"], a["ws"], a["wsb"], None)
+    assert sample(x=None) == -1 and sample(tok=None) == -1 and sample(ws=None) == -1
+    assert sample(dt=7) == -3 and sample(T=0.0) == -2 and sample(npos=0) == -2 and sample(pos0=-1) == -2
+    assert sample(pos0=2**31 - 2) == -2 and sample(x=FAKE + 2) == -4 and sample(wsb=4) == -5
+    assert L.ersd_race_sample_workspace_bytes(2, 1, 3, 64, 1) > 0
+    assert L.ersd_race_sample_workspace_bytes(0, 1, 3, 64, 1) == 0 and L.ersd_race_sample_workspace_bytes(2, 1, 3, 64, 4) == 0
+    acc = L.ersd_accept_lengths
+    assert acc(0, 2, 1, 3, None, None, FAKE, FAKE, None, None, None, None) == -1
+    assert acc(0, 2, 1, 3, None, FAKE, FAKE, None, None, None, None, None) == -1
+    assert acc(2, 2, 1, 3, None, FAKE, FAKE, FAKE, None, None, None, None) == -1      # tree without parent
+    assert acc(1, 2, 2, 3, None, FAKE, FAKE, FAKE, None, None, None, None) == -1      # multi without best outputs
+    assert acc(0, 0, 1, 3, None, FAKE, FAKE, FAKE, None, None, None, None) == -2 and acc(5, 2, 1, 3, None, FAKE, FAKE, FAKE, None, None, None, None) == -2
 
 
 def test_workspace_bytes(L):

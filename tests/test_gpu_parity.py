@@ -217,3 +217,50 @@ def test_full_size_workloads_match_oracle(race, oracle_mod, idx):
     gpu, ora, ex = run_case(race, oracle_mod, w, note="(full size)")
     acc = gpu[2].cpu().numpy()
     print(f"[full] {w.name}: mean accept_len {acc.mean():.3f}, exempted rows {ex}", flush=True)
+
+
+def test_one_model_races_and_acceptance_step_equal_the_fused_calls(race, oracle_mod):
+    """Drafting position by position with the draft model, racing the target rows afterwards and running the
+    acceptance step on the tokens gives exactly what the fused verify calls give (and what the oracle gives)."""
+    # sequence / multi
+    w = wl.shrink(wl.WORKLOADS[3], B=3, m=2, k=3, V=10240)
+    x = wl.make_inputs(w, "cuda")
+    T, seed = w.temperature, w.seed
+    fused = [v.cpu() for v in race.race_verify_multi(x["draft"], x["target"], T, seed)]
+    steps = [race.race_sample(x["draft"][:, :, j:j + 1].contiguous(), j, T, seed) for j in range(w.k)]
+    dtok = torch.cat(steps, dim=2).contiguous()
+    ttok = race.race_sample(x["target"], 0, T, seed)
+    acc, bd, bl = race.accept_lengths(race.VARIANT_MULTI, dtok, ttok)
+    for got, ref in zip((dtok, ttok, acc, bd, bl), fused):
+        assert torch.equal(got.cpu(), ref)
+    o_d = oracle_mod.race_sample(x["draft"].cpu(), 0, T, seed)
+    o_t = oracle_mod.race_sample(x["target"].cpu(), 0, T, seed)
+    assert np.array_equal(dtok.cpu().numpy(), o_d) and np.array_equal(ttok.cpu().numpy(), o_t)
+    # whole draft tensor in one call, fp32 and an odd vocabulary (element loads)
+    w2 = wl.shrink(wl.WORKLOADS[0], B=2, k=3, V=4999)
+    y = wl.make_inputs(w2, "cuda")
+    fd, ft, fa = race.race_verify(y["draft"], y["target"], 1.0, 5)
+    sd = race.race_sample(y["draft"].unsqueeze(1).contiguous(), 0, 1.0, 5)[:, 0]
+    st = race.race_sample(y["target"].unsqueeze(1).contiguous(), 0, 1.0, 5)[:, 0]
+    assert torch.equal(sd, fd) and torch.equal(st, ft)
+    assert torch.equal(race.accept_lengths(race.VARIANT_SEQUENCE, sd.contiguous(), st.contiguous()), fa)
+    # tree: positions are node indices
+    w3 = wl.shrink(wl.WORKLOADS[4], B=2, N=12, V=8192)
+    z = wl.make_inputs(w3, "cuda")
+    td, tt, ta, tn = race.race_verify_tree(z["draft"], z["target"], z["parent"], 1.0, 9)
+    sd = race.race_sample(z["draft"].unsqueeze(1).contiguous(), 0, 1.0, 9)[:, 0].contiguous()
+    st = race.race_sample(z["target"].unsqueeze(1).contiguous(), 0, 1.0, 9)[:, 0].contiguous()
+    assert torch.equal(sd, td) and torch.equal(st, tt)
+    a2, n2 = race.accept_lengths(race.VARIANT_TREE, sd, st, z["parent"])
+    assert torch.equal(a2, ta) and torch.equal(n2, tn)
+
+
+def test_one_model_race_full_size_target_rows(race, oracle_mod):
+    """Target-only races at the headline shape (B=64, 9 positions, V=128256, bf16) against the oracle."""
+    w = wl.WORKLOADS[1]
+    x = wl.make_inputs(w, "cuda")
+    tok = race.race_sample(x["target"].unsqueeze(1).contiguous(), 0, w.temperature, w.seed)
+    torch.cuda.synchronize()
+    ref, info = oracle_mod.race_sample(x["target"].unsqueeze(1).contiguous().cpu(), 0, w.temperature, w.seed, want_info=True)
+    assert info["near_tie"].sum() == 0
+    assert np.array_equal(tok.cpu().numpy(), ref)

@@ -221,3 +221,23 @@ def test_seed_and_counter_words_select_independent_races(oracle_mod):
     assert len(set(toks.values())) > 20           # 32 contexts, nearly all distinct winners on a flat-ish row
     # high and low seed words both matter
     assert toks[(0, 0, 0, 0)] != toks[(2**32, 0, 0, 0)] or toks[(0, 1, 0, 0)] != toks[(2**32, 1, 0, 0)]
+
+
+def test_one_model_races_reproduce_the_two_model_race(oracle_mod):
+    """Algorithm 2 runs the draft race before the target model is evaluated and the target race after it, on the
+    same exponentials: racing each model's rows separately must give the fused result, also position by position."""
+    rng = np.random.default_rng(13)
+    B, m, k, V = 3, 2, 4, 200
+    t = rng.normal(0, 2.5, size=(B, m, k + 1, V)).astype(np.float32)
+    d = (t[:, :, :k] + rng.normal(0, 0.6, size=(B, m, k, V))).astype(np.float32)
+    fused = oracle_mod.race_verify_multi(d, t, 0.9, 31)
+    assert np.array_equal(oracle_mod.race_sample(d, 0, 0.9, 31), fused["draft_tokens"])
+    assert np.array_equal(oracle_mod.race_sample(t, 0, 0.9, 31), fused["target_tokens"])
+    for j in range(k):      # a drafting loop: one position per call
+        step = oracle_mod.race_sample(np.ascontiguousarray(d[:, :, j:j + 1]), j, 0.9, 31)
+        assert np.array_equal(step[:, :, 0], fused["draft_tokens"][:, :, j])
+    # and against the independent pure-Python statement
+    e = mini_oracle.exponentials(V, 31, 2, 1, 1, rounds=oracle_mod.get_rounds())
+    assert fused["target_tokens"][1, 1, 2] == mini_oracle.race_winner(t[1, 1, 2].astype(np.float64), 0.9, e)
+    with pytest.raises(ValueError):
+        oracle_mod.race_sample(d, -1, 0.9, 31)
