@@ -67,6 +67,11 @@ def lib():
         L.oracle_race_verify_tree.argtypes = [vp, vp, ctypes.c_int, i32, i32, i64, vp, f32, u64,
                                               vp, vp, vp, vp, vp, vp]
         L.oracle_race_verify_tree.restype = ctypes.c_int
+        L.oracle_race_verify_arrival_tree.argtypes = [vp, vp, ctypes.c_int, i32, i32, i64, vp, vp, i32, f32, u64,
+                                                      vp, vp, vp, vp, vp, vp, vp, vp]
+        L.oracle_race_verify_arrival_tree.restype = ctypes.c_int
+        L.oracle_arrival_tree_shape.argtypes = [vp, vp, i32, i32, vp, vp]
+        L.oracle_arrival_tree_shape.restype = None
         L.oracle_num_threads.restype = ctypes.c_int
         L.oracle_set_num_threads.argtypes = [ctypes.c_int]
         _LIB = L
@@ -243,4 +248,46 @@ def race_verify_tree(draft, target, parent, temperature, seed, want_info=False):
     out = dict(draft_tokens=dtok, target_tokens=ttok, accept_len=acc, accept_node=node)
     if want_info:
         out.update(draft_info=di, target_info=ti)
+    return out
+
+
+def arrival_tree_shape(parent, rank, max_rank=8):
+    """-> (valid [N], need [N+1]) of a (parent, rank) tree."""
+    par = np.ascontiguousarray(np.asarray(parent, dtype=np.int32))
+    rk = np.ascontiguousarray(np.asarray(rank, dtype=np.int32))
+    N = par.shape[0]
+    valid = np.zeros(N, dtype=np.int32)
+    need = np.zeros(N + 1, dtype=np.int32)
+    lib().oracle_arrival_tree_shape(_ptr(par), _ptr(rk), N, int(max_rank), _ptr(valid), _ptr(need))
+    return valid, need
+
+
+def race_verify_arrival_tree(draft, target, parent, rank, temperature, seed, max_rank=8, want_info=False):
+    """Algorithm 5: draft, target [B,N+1,V] (one row per context); parent, rank int32 [N]."""
+    d, dt = _host(draft)
+    t, dt2 = _host(target)
+    assert dt == dt2
+    B, C, V = d.shape
+    N = C - 1
+    assert t.shape == (B, C, V)
+    par = np.ascontiguousarray(np.asarray(parent, dtype=np.int32))
+    rk = np.ascontiguousarray(np.asarray(rank, dtype=np.int32))
+    assert par.shape == (N,) and rk.shape == (N,)
+    arr = np.zeros((B, C, max_rank), dtype=np.int32)
+    dtok = np.zeros((B, N), dtype=np.int32)
+    ttok = np.zeros((B, C), dtype=np.int32)
+    acc = np.zeros(B, dtype=np.int32)
+    node = np.zeros(B, dtype=np.int32)
+    emitted = np.zeros((B, C), dtype=np.int32)
+    near = np.zeros((B, C), dtype=np.int32) if want_info else None
+    ti = np.zeros((B, C), dtype=ROW_INFO_DTYPE) if want_info else None
+    rc = lib().oracle_race_verify_arrival_tree(_ptr(d), _ptr(t), dt, B, N, V, _ptr(par), _ptr(rk), int(max_rank),
+                                               float(temperature), int(seed), _ptr(arr), _ptr(dtok), _ptr(ttok),
+                                               _ptr(acc), _ptr(node), _ptr(emitted),
+                                               _ptr(near) if want_info else None, _ptr(ti) if want_info else None)
+    if rc != 0:
+        raise ValueError("oracle_race_verify_arrival_tree: invalid arguments")
+    out = dict(arrivals=arr, draft_tokens=dtok, target_tokens=ttok, accept_len=acc, accept_node=node, emitted=emitted)
+    if want_info:
+        out.update(arrival_near_tie=near, target_info=ti)
     return out

@@ -9,6 +9,7 @@
 
 #include <math.h>
 #include <stddef.h>
+#include <stdlib.h>
 #include <string.h>
 #ifdef _OPENMP
 #include <omp.h>
@@ -306,5 +307,121 @@ int oracle_race_verify_tree(const void* draft, const void* target, int dtype,
         accept_len[b] = best_depth;
         if (accept_node) accept_node[b] = best_node;
     }
+    return 0;
+}
+
+/* ---- Algorithm 5 as printed: one race per context, the children of a context are its first arrivals under Q ---- */
+
+void oracle_arrival_tree_shape(const int32_t* parent, const int32_t* rank, int32_t N, int32_t max_rank,
+                               int32_t* valid, int32_t* need) {
+    for (int32_t c = 0; c <= N; ++c) need[c] = 0;
+    for (int32_t n = 0; n < N; ++n) {
+        const int32_t p = parent[n], r = rank[n];
+        int ok = p >= -1 && p < n && r >= 0 && r < max_rank && (p == -1 || valid[p]);
+        for (int32_t o = 0; ok && o < n; ++o) /* an earlier sibling already holds this arrival */
+            if (valid[o] && parent[o] == p && rank[o] == r) ok = 0;
+        valid[n] = ok;
+        if (ok && r + 1 > need[p + 1]) need[p + 1] = r + 1;
+    }
+}
+
+/* position of (score a, index ia) after (score b, index ib) in the order of arrival: earlier arrival = larger score,
+ * equal scores in index order */
+static int arrives_after(double a, int64_t ia, double b, int64_t ib) { return a < b || (a == b && ia > ib); }
+
+int oracle_race_verify_arrival_tree(const void* draft, const void* target, int dtype, int32_t B, int32_t N, int64_t V,
+                                    const int32_t* parent, const int32_t* rank, int32_t max_rank,
+                                    float temperature, uint64_t seed,
+                                    int32_t* arrivals, int32_t* draft_tokens, int32_t* target_tokens,
+                                    int32_t* accept_len, int32_t* accept_node, int32_t* emitted,
+                                    int32_t* arrival_near_tie, oracle_row_info* target_info) {
+    if (bad_common(draft, target, dtype, V, temperature)) return -1;
+    if (B < 1 || N < 1 || max_rank < 1 || !parent || !rank || !arrivals || !draft_tokens || !target_tokens ||
+        !accept_len || !accept_node || !emitted)
+        return -1;
+    const size_t es = elem_size(dtype);
+    const int32_t C = N + 1; /* contexts: 0 = the partial output itself, n + 1 = the path that ends at node n */
+    int32_t* valid = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
+    int32_t* need = (int32_t*)malloc(sizeof(int32_t) * (size_t)C);
+    if (!valid || !need) { free(valid); free(need); return -1; }
+    oracle_arrival_tree_shape(parent, rank, N, max_rank, valid, need);
+    const uint32_t key[2] = {(uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32)};
+    const double T = (double)temperature;
+    const int64_t nrace = (int64_t)B * C;
+    if (g_threads > 0) {
+#ifdef _OPENMP
+        omp_set_num_threads(g_threads);
+#endif
+    }
+    int failed = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t r = 0; r < nrace; ++r) {
+        const int32_t c = (int32_t)(r % C);
+        const int32_t b = (int32_t)(r / C);
+        /* winner under P of the race of context c */
+        const void* rows[2] = {NULL, (const char*)target + (size_t)(r * V) * es};
+        oracle_row_info info[2];
+        oracle_race_rows(rows, dtype, V, temperature, seed, (uint32_t)c, (uint32_t)b, 0u, info);
+        target_tokens[r] = info[1].token;
+        if (target_info) target_info[r] = info[1];
+        for (int32_t a = 0; a < max_rank; ++a) arrivals[r * max_rank + a] = -1;
+        if (arrival_near_tie) arrival_near_tie[r] = 0;
+        if (need[c] == 0) continue; /* no child: Q is not evaluated at this context */
+        /* the same race under Q: every token's score, then the first need[c] arrivals one after the other */
+        const char* qrow = (const char*)draft + (size_t)(r * V) * es;
+        double* s = (double*)malloc(sizeof(double) * (size_t)V);
+        if (!s) { failed = 1; continue; }
+        uint32_t words[4] = {0, 0, 0, 0};
+        for (int64_t i = 0; i < V; ++i) {
+            if ((i & 3) == 0) {
+                const uint32_t ctr[4] = {(uint32_t)(i >> 2), (uint32_t)c, (uint32_t)b, 0u};
+                oracle_philox4x32(g_rounds, ctr, key, words);
+            }
+            s[i] = widen(qrow, dtype, i) / T + oracle_gumbel(words[i & 3]);
+        }
+        double ps = INFINITY;
+        int64_t pi = -1;
+        for (int32_t a = 0; a <= need[c]; ++a) { /* one more than needed, to see how close the next one was */
+            int64_t bi = -1;
+            for (int64_t i = 0; i < V; ++i) {
+                if (!(s[i] > -INFINITY)) continue; /* a token outside the support never arrives */
+                if (a > 0 && !arrives_after(s[i], i, ps, pi)) continue;
+                if (bi < 0 || s[i] > s[bi]) bi = i;
+            }
+            if (bi < 0) break;
+            if (a > 0 && arrival_near_tie) {
+                const double scale = fabs(ps) > 1.0 ? fabs(ps) : 1.0;
+                if (ps == s[bi] || ps - s[bi] <= 1e-6 * scale) arrival_near_tie[r] = 1;
+            }
+            if (a < need[c]) arrivals[r * max_rank + a] = (int32_t)bi;
+            ps = s[bi];
+            pi = bi;
+        }
+        free(s);
+    }
+    if (failed) { free(valid); free(need); return -1; }
+    for (int32_t b = 0; b < B; ++b) {
+        for (int32_t n = 0; n < N; ++n)
+            draft_tokens[(int64_t)b * N + n] =
+                valid[n] ? arrivals[((int64_t)b * C + parent[n] + 1) * max_rank + rank[n]] : -1;
+        /* verification walk: emit the winner under P; go on from the child that drafted it, if there is one */
+        for (int32_t c = 0; c < C; ++c) emitted[(int64_t)b * C + c] = -1;
+        int32_t ctx = 0, len = 0, node = -1;
+        while (1) {
+            const int32_t t = target_tokens[(int64_t)b * C + ctx];
+            emitted[(int64_t)b * C + len] = t;
+            int32_t next = -1;
+            for (int32_t n = 0; n < N && next < 0; ++n)
+                if (valid[n] && parent[n] + 1 == ctx && draft_tokens[(int64_t)b * N + n] == t) next = n;
+            if (next < 0) break;
+            ++len;
+            node = next;
+            ctx = next + 1;
+        }
+        accept_len[b] = len;
+        accept_node[b] = node;
+    }
+    free(valid);
+    free(need);
     return 0;
 }

@@ -118,6 +118,36 @@ int oracle_race_verify_tree(const void* draft, const void* target, int dtype,
                             int32_t* accept_len, int32_t* accept_node,
                             oracle_row_info* draft_info, oracle_row_info* target_info);
 
+/*
+ * Tree form as Algorithm 5 states it (Section 3: the batch strategy takes the first arrivals of ONE race under Q
+ * as the alternatives at a context, and the tree strategy continues each of them).
+ *   Contexts: c = 0 is the partial output, c = n + 1 the path that ends at node n; C = N + 1.  Context c has one
+ *   race, counter words (i >> 2, c, b, 0).  draft and target are [B,C,V]; draft row (b,c) is read only if c has a
+ *   child.  Node n is the child of context parent[n] + 1 that holds arrival number rank[n] (0 = the winner) of that
+ *   context's race under Q: tokens ordered by decreasing score l_q/T - ln e, equal scores by increasing index;
+ *   a token whose score is -inf (outside the support) never arrives, and a missing arrival is token -1.
+ *   Node n is valid iff -1 <= parent[n] < n, the parent is valid, 0 <= rank[n] < max_rank and no earlier valid
+ *   sibling has the same rank; an invalid node has draft token -1 and is never accepted.
+ *   Walk (the listing's second loop, reading its race as the one under P, as its comment says, and moving on to the
+ *   matching child): at the current context emit the winner under P; if a valid child drafted that token, accept
+ *   it and continue at the child's context, else stop.
+ * Outputs: arrivals [B,C,max_rank] (the first need[c] arrivals, -1 elsewhere), draft_tokens [B,N],
+ * target_tokens [B,C], accept_len [B] = accepted drafted tokens, accept_node [B] = last accepted node (-1 if none),
+ * emitted [B,C] = the accept_len + 1 tokens the step produces, then -1.
+ * arrival_near_tie [B,C] (may be NULL): 1 iff two consecutive arrivals among the first need[c] + 1 are closer than
+ * 1e-6 * max(1, |score|).  target_info [B,C] may be NULL.
+ */
+int oracle_race_verify_arrival_tree(const void* draft, const void* target, int dtype, int32_t B, int32_t N, int64_t V,
+                                    const int32_t* parent, const int32_t* rank, int32_t max_rank,
+                                    float temperature, uint64_t seed,
+                                    int32_t* arrivals, int32_t* draft_tokens, int32_t* target_tokens,
+                                    int32_t* accept_len, int32_t* accept_node, int32_t* emitted,
+                                    int32_t* arrival_near_tie, oracle_row_info* target_info);
+
+/* valid[N] and need[N+1] (arrivals wanted per context) of a (parent, rank) tree, by the rule above. */
+void oracle_arrival_tree_shape(const int32_t* parent, const int32_t* rank, int32_t N, int32_t max_rank,
+                               int32_t* valid, int32_t* need);
+
 /* Threads the row loops will use (OpenMP), for reporting. */
 int oracle_num_threads(void);
 void oracle_set_num_threads(int n);

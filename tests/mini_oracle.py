@@ -86,3 +86,57 @@ def tree_accept(dtok, ttok, parent):
         if ok and all(dtok[x] == ttok[x] for x in path) and len(path) > best_len:
             best_len, best_node = len(path), n
     return best_len, best_node
+
+
+def arrival_tree(draft, target, parent, rank, T, seed, max_rank=8, rounds=7):
+    """Algorithm 5 in its literal form: arrival times e_i / q_i, children = first arrivals under Q.
+
+    draft, target [B,N+1,V] float64 (row c = context c: 0 the partial output, n+1 the path ending at node n).
+    -> (draft_tokens [B,N], target_tokens [B,N+1], accept_len [B], accept_node [B], emitted list of lists)
+    """
+    B, C, V = draft.shape
+    N = C - 1
+    valid = [False] * N
+    for n in range(N):
+        p, r = parent[n], rank[n]
+        ok = -1 <= p < n and 0 <= r < max_rank and (p == -1 or valid[p])
+        ok = ok and not any(valid[o] and parent[o] == p and rank[o] == r for o in range(n))
+        valid[n] = ok
+    dtok = -np.ones((B, N), dtype=np.int32)
+    ttok = np.zeros((B, C), dtype=np.int32)
+    acc = np.zeros(B, dtype=np.int32)
+    node = -np.ones(B, dtype=np.int32)
+    emitted = []
+    Tf = float(np.float32(T))
+    for b in range(B):
+        order = []
+        for c in range(C):
+            e = exponentials(V, seed, c, b, 0, rounds)
+            ttok[b, c] = race_winner(target[b, c], T, e)
+            z = np.asarray(draft[b, c], dtype=np.float64) / Tf
+            if np.all(np.isneginf(z)):
+                order.append([])
+                continue
+            q = np.exp(z - z.max())
+            q = q / q.sum()
+            with np.errstate(divide="ignore"):
+                t = np.where(q > 0, e / q, np.inf)
+            idx = np.argsort(t, kind="stable")
+            order.append([int(i) for i in idx if np.isfinite(t[i])])
+        for n in range(N):
+            if valid[n]:
+                o = order[parent[n] + 1]
+                dtok[b, n] = o[rank[n]] if rank[n] < len(o) else -1
+        ctx, y, last = 0, [], -1
+        while True:
+            t = int(ttok[b, ctx])
+            y.append(t)
+            nxt = [n for n in range(N) if valid[n] and parent[n] + 1 == ctx and dtok[b, n] == t]
+            if not nxt:
+                break
+            last = nxt[0]
+            ctx = last + 1
+        emitted.append(y)
+        acc[b] = len(y) - 1
+        node[b] = last
+    return dtok, ttok, acc, node, emitted
