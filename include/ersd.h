@@ -72,6 +72,10 @@ typedef enum {
 
 typedef enum { ERSD_VARIANT_SEQUENCE = 0, ERSD_VARIANT_MULTI = 1, ERSD_VARIANT_TREE = 2 } ersd_variant;
 
+/* Arrival trees (Algorithm 5): largest number of arrivals of one race a tree may use, and largest tree. */
+#define ERSD_MAX_RANK 8
+#define ERSD_MAX_ARRIVAL_TREE_NODES 8192
+
 /*
  * Bytes of device workspace the matching verify call needs (surviving candidates of row segments).
  * `m` is ignored for the sequence and tree variants, `k_or_N` is k (sequence, multi) or N (tree).
@@ -185,6 +189,45 @@ size_t ersd_race_sample_workspace_bytes(int32_t B, int32_t m, int32_t npos, int3
 int ersd_accept_lengths(int variant, int32_t B, int32_t m, int32_t k_or_N, const int32_t* parent,
                         const int32_t* draft_tokens, const int32_t* target_tokens, int32_t* accept_len,
                         int32_t* best_draft, int32_t* best_len, int32_t* accept_node, void* stream);
+
+/*
+ * Tree verification as Algorithm 5 states it (Section 3: the batch strategy takes the first arrivals of ONE
+ * race under the draft model as the alternatives at a context; the tree strategy continues each of them).
+ * This is the form for which the emitted tokens keep the target model's distribution.
+ *   Contexts: c = 0 is the partial output, c = n + 1 the path that ends at node n; C = N + 1.  Context c has
+ *   one race, counter words (i >> 2, c, b, 0).
+ *   draft_logits, target_logits [B, C, V]; draft row (b, c) is read only if context c has a valid child.
+ *   parent, rank [N] (DEVICE, shared by all prompts): node n is the child of context parent[n] + 1 that holds
+ *   arrival number rank[n] (0 = the winner) of that context's race under the draft model.  Arrivals are ordered
+ *   by decreasing score logit/T - ln e, equal scores by increasing token index; a token whose score is -inf
+ *   never arrives, and a missing arrival is token -1.  Node n is valid iff -1 <= parent[n] < n, its parent is
+ *   valid, 0 <= rank[n] < ERSD_MAX_RANK and no earlier valid sibling has the same rank; an invalid node gets
+ *   draft token -1 and is never accepted.  N <= ERSD_MAX_ARRIVAL_TREE_NODES.
+ *   draft_tokens [B, N] out: the token each node drafts.  target_tokens [B, C] out: the winner of each
+ *   context's race under the target model.
+ *   Walk (the listing's second loop, with the race under the target model as its comment says, continuing at
+ *   the matching child): at the current context emit the target winner; if a valid child drafted that token,
+ *   accept it and go on at that child's context, else stop.
+ *   accept_len [B] out: accepted drafted tokens.  accept_node [B] out: last accepted node, -1 if none.
+ *   emitted [B, C] out: the accept_len + 1 tokens the step produces (accepted tokens, then the correction or
+ *   bonus token), then -1.
+ * A chain with all ranks 0 gives exactly ersd_race_verify (draft rows 0 .. N-1, target rows 0 .. N).
+ * Workspace size: ersd_race_arrival_tree_workspace_bytes (0 for invalid sizes).  Same memory, stream and
+ * error rules as ersd_race_verify; the tree is examined on the device, nothing is read back.
+ */
+int ersd_race_verify_arrival_tree(const void* draft_logits, const void* target_logits, ersd_dtype dt,
+                                  int32_t B, int32_t N, int32_t V, const int32_t* parent, const int32_t* rank,
+                                  float temperature, uint64_t seed,
+                                  int32_t* draft_tokens, int32_t* target_tokens, int32_t* accept_len,
+                                  int32_t* accept_node, int32_t* emitted,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+size_t ersd_race_arrival_tree_workspace_bytes(int32_t B, int32_t N, int32_t V, ersd_dtype dt);
+
+/* Host helper: 1 if every node of (parent, rank)[0..N) (HOST arrays) is valid by the rule above, else 0. */
+int ersd_arrival_tree_validate_host(const int32_t* parent_host, const int32_t* rank_host, int32_t N);
+
+/* ERSD_MAX_RANK of the loaded library. */
+int ersd_max_rank(void);
 
 /*
  * Device self-check of the two single-precision bounds the streaming filter relies on, over all 2^32

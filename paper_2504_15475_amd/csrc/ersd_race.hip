@@ -66,6 +66,9 @@ constexpr uint32_t kPhiloxM0 = 0xD2511F53u, kPhiloxM1 = 0xCD9E8D57u;
 constexpr uint32_t kPhiloxW0 = 0x9E3779B9u, kPhiloxW1 = 0xBB67AE85u;
 
 constexpr int kMaxSurvivors = 4;
+constexpr int kMaxRank = ERSD_MAX_RANK;             // arrivals of one race a tree may use (Algorithm 5's child ranks)
+constexpr int kMaxArrSurvivors = 16;                // survivors a segment hands on when the first arrivals are wanted
+constexpr int32_t kMaxArrNodes = ERSD_MAX_ARRIVAL_TREE_NODES;
 
 // What a row segment hands to the finishing kernel for one side: the tokens that can still be the row maximum.
 struct Cand {
@@ -79,6 +82,11 @@ struct SegOut {
     int32_t pad[3];
     Cand c[kMaxSurvivors];
 };
+struct SegOutArr {   // the same for a draft row of which the first arrivals (not only the winner) are wanted
+    int32_t count;
+    int32_t pad[3];
+    Cand c[kMaxArrSurvivors];
+};
 
 // Balanced partition of the concatenated rows (in 8-token groups) over G workgroups.  Shared by the race
 // kernel (which part is mine, which slot do I write) and the finishing kernel (which slots does a row have).
@@ -91,13 +99,30 @@ struct Part {
     uint32_t kd, kt;      // draft rows / target rows per sequence
     uint32_t G;           // workgroups
     uint32_t nslot;       // partial slots per (row, side)
+    // Arrival trees: which contexts have a draft row is known on the device only.  wprefix[c] = summed weights of
+    // the contexts before c (kt + 1 entries, device memory); nullptr for the closed-form layouts above.
+    const uint32_t* wprefix;
 };
+
+// context whose cost units contain weighted position wpos (in units of one group): largest c with wprefix[c] <= wpos
+__host__ __device__ inline uint32_t part_table_row(const Part& p, uint64_t wpos) {
+    uint32_t lo = 0, hi = p.kt;  // answer in [lo, hi)
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if ((uint64_t)p.wprefix[mid] <= wpos) lo = mid;
+        else hi = mid;
+    }
+    return lo;
+}
 
 __host__ __device__ inline uint64_t part_unit_to_pos(const Part& p, uint64_t u) {
     if (u >= p.U) return p.rows * p.V8;
     const uint64_t seq = u / p.Us, rem = u % p.Us;
     uint64_t row, grp;
-    if (rem < p.pair_units) {
+    if (p.wprefix) {
+        row = part_table_row(p, rem / p.V8);
+        grp = (rem - (uint64_t)p.wprefix[row] * p.V8) / (p.wprefix[row + 1] - p.wprefix[row]);
+    } else if (rem < p.pair_units) {
         row = rem / ((uint64_t)kWPair * p.V8);
         grp = (rem % ((uint64_t)kWPair * p.V8)) / kWPair;
     } else {
@@ -114,6 +139,10 @@ __host__ __device__ inline uint64_t part_start_pos(const Part& p, uint32_t b) {
 __host__ __device__ inline uint64_t part_row_unit(const Part& p, uint64_t row, uint32_t* w) {
     const uint64_t seq = row / p.kt;
     const uint32_t j = (uint32_t)(row % p.kt);
+    if (p.wprefix) {
+        *w = p.wprefix[j + 1] - p.wprefix[j];
+        return seq * p.Us + (uint64_t)p.wprefix[j] * p.V8;
+    }
     *w = j < p.kd ? kWPair : kWSingle;
     return seq * p.Us + (j < p.kd ? (uint64_t)j * kWPair * p.V8 : p.pair_units + (uint64_t)(j - p.kd) * kWSingle * p.V8);
 }
@@ -142,6 +171,9 @@ struct RaceArgs {
     float c2;           // log2(e) / T
     int32_t exhaustive; // score every token in fp64 (reference path for tests)
     double T;
+    // arrival trees only
+    SegOutArr* outq;       // [row][slot]: draft-side survivors
+    const int32_t* need;   // [kt]: arrivals wanted per context (0: the context has no child, its draft row is not read)
 };
 
 // ------------------------------------------------------------------------------------------ Philox4x32-R
@@ -199,6 +231,7 @@ struct Seg {
     int32_t begin, end;  // token range, begin a multiple of 8
     uint64_t row;
     uint32_t slot;
+    int32_t nq;          // arrival trees: arrivals wanted from the draft row (>= 1); 0 = only the winner, plain mode
 };
 
 struct Lds {
@@ -208,13 +241,40 @@ struct Lds {
     uint32_t word[2][kListCap];
     float logit[2][kListCap];
     int32_t nsurv[2];
-    int32_t surv[2][kMaxSurvivors];  // list positions of the survivors
+    int32_t surv[2][kMaxArrSurvivors];  // list positions of the survivors
     double red_s[kWaves];
     int32_t red_i[kWaves];
+    float top[kMaxRank];  // arrival trees: lower bounds of nq distinct draft-side tokens (see top_insert)
+    int32_t rounds;       // arrival trees: exact selection rounds the segment's epilogue needs
 };
 
 // Exact scan of one side of a segment: every token scored in fp64.  The reference path, and the fallback when
 // a candidate list overflows.  Waves 0-1 take side 0, waves 2-3 side 1 (lane best only; reduced by the caller).
+// true iff (s, i) arrives after (ps, pi): smaller score, or the same score and a higher index
+__device__ __forceinline__ bool arrives_after(double s, int32_t i, double ps, int32_t pi) {
+    return s < ps || (s == ps && i > pi);
+}
+
+// The same restricted to the tokens that arrive after (ps, pi) and have a finite score: the next arrival.
+template <int DT>
+__device__ void exhaustive_half_after(const RaceArgs& a, const Seg& c, const char* row, int half_tid, bool has_prev,
+                                      double ps, int32_t pi, double& bs, int32_t& bi) {
+    const int32_t g0 = c.begin >> 2, g1 = (c.end + 3) >> 2;
+    for (int32_t g = g0 + half_tid; g < g1; g += kThreads / 2) {
+        uint32_t w[4];
+        philox4x32((uint32_t)g, c.c1, c.c2, c.c3, a.key0, a.key1, w);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int32_t i = g * 4 + e;
+            if (i < c.end) {
+                const double s = exact_score(widen_elem(row, DT, i), a.T, w[e]);
+                if (!(s > -INFINITY) || (has_prev && !arrives_after(s, i, ps, pi))) continue;
+                if (bi < 0 || s > bs) { bs = s; bi = i; }
+            }
+        }
+    }
+}
+
 template <int DT>
 __device__ void exhaustive_half(const RaceArgs& a, const Seg& c, const char* row, int half_tid, double& bs,
                                 int32_t& bi) {
@@ -358,9 +418,43 @@ __device__ __forceinline__ void lds_tau_raise(Lds& lds, int side, float v) {
     __hip_atomic_fetch_max(&lds.tau[side], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
-// One side's refine step for one token of one lane.
+// Arrival trees, draft side: tau must stay below the nq-th largest score of the segment.  lds.top holds lower
+// bounds of up to nq DISTINCT tokens: every token is refined at most once and a bound enters only here, so the
+// smallest of nq entries is below the nq-th largest score.  The lanes of a wavefront take turns; other wavefronts
+// may interleave, which can lose an entry or mix two states in one read, but every value read is still the bound
+// of a distinct token, so the returned bound (kTauInit if none) is valid whatever the interleaving.
+__device__ __forceinline__ float top_insert(Lds& lds, int32_t nq, float lb) {
+    float result = kTauInit;
+    uint64_t todo = __builtin_amdgcn_ballot_w64(true);  // the lanes that are here
+    const int lane = threadIdx.x & (kWave - 1);
+    while (todo) {
+        const int leader = __builtin_ctzll(todo);
+        todo &= todo - 1;
+        if (lane == leader) {
+            float v[kMaxRank];
+            float m = INFINITY;
+            int am = 0;
+#pragma unroll
+            for (int r = 0; r < kMaxRank; ++r) {
+                v[r] = r < nq ? __hip_atomic_load(&lds.top[r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) : INFINITY;
+                if (v[r] < m) { m = v[r]; am = r; }
+            }
+            if (lb > m) {  // replaces the smallest entry (false for a NaN bound)
+                __hip_atomic_store(&lds.top[am], lb, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                float m2 = lb;
+#pragma unroll
+                for (int r = 0; r < kMaxRank; ++r)
+                    if (r != am) m2 = fminf(m2, v[r]);
+                result = m2;
+            }
+        }
+    }
+    return result;
+}
+
+// One side's refine step for one token of one lane.  nq > 0: the nq first arrivals are wanted, not only the winner.
 __device__ __forceinline__ void refine_token(float logit, uint32_t x, float l2e, float c2, int32_t idx, float& tau,
-                                             Lds& lds, int side) {
+                                             Lds& lds, int side, int32_t nq) {
     const float s2 = fmaf(logit, c2, -l2e);
     const float err = refine_err(s2);
     if (s2 > -INFINITY && s2 + err >= tau) {
@@ -370,7 +464,7 @@ __device__ __forceinline__ void refine_token(float logit, uint32_t x, float l2e,
             lds.word[side][pos] = x;
             lds.logit[side][pos] = logit;
         }
-        tau = fmaxf(tau, s2 - err);
+        tau = fmaxf(tau, nq > 0 ? top_insert(lds, nq, s2 - err) : s2 - err);
     }
 }
 
@@ -404,7 +498,7 @@ template <bool RAWF32, bool HASQ>
 __device__ __forceinline__ void refine_tile(Lds& lds, float c2, int32_t i0, int32_t i1, int32_t end, const Raw& rq,
                                             const Raw& rp, const uint32_t (&x)[8], const float (&up)[8],
                                             const float (&uq)[8], bool flag, float tauq_m, float taup_m, float& tauq,
-                                            float& taup) {
+                                            float& taup, int32_t nq) {
     if (!flag) return;
     // which of this lane's (token, side) bounds reach tau: bits 0-7 target side, 8-15 draft side
     uint32_t mask = 0;
@@ -425,7 +519,7 @@ __device__ __forceinline__ void refine_tile(Lds& lds, float c2, int32_t i0, int3
             const float lq = HASQ ? raw_logit<RAWF32>(rq, e) : 0.0f;
             const float lp = raw_logit<RAWF32>(rp, e);
             float tau = isq ? tauq : taup;
-            refine_token(isq ? lq : lp, xe, log2_exponential(xe), c2, idx, tau, lds, isq ? 0 : 1);
+            refine_token(isq ? lq : lp, xe, log2_exponential(xe), c2, idx, tau, lds, isq ? 0 : 1, isq ? nq : 0);
             if (isq) tauq = tau;
             else taup = tau;
         }
@@ -436,7 +530,7 @@ __device__ __forceinline__ void refine_tile(Lds& lds, float c2, int32_t i0, int3
 }
 
 // The per-iteration work of one lane: 8 tokens of one or two rows.
-template <bool RAWF32, bool HASQ>
+template <bool RAWF32, bool HASQ, bool ARR>
 __device__ __forceinline__ void filter_tile(const RaceArgs& a, const Seg& c, Lds& lds, const HotConsts& h, int32_t i0,
                                             int32_t i1, const Raw& rq, const Raw& rp, float& tauq, float& taup) {
     const float c2 = h.c2;
@@ -466,12 +560,13 @@ __device__ __forceinline__ void filter_tile(const RaceArgs& a, const Seg& c, Lds
     if (HASQ) flag = flag || (accq >= tauq_m);
 
     if (__builtin_amdgcn_ballot_w64(flag) != 0)  // rare: some lane holds a token that may matter
-        refine_tile<RAWF32, HASQ>(lds, a.c2, i0, i1, c.end, rq, rp, x, up, uq, flag, tauq_m, taup_m, tauq, taup);
+        refine_tile<RAWF32, HASQ>(lds, a.c2, i0, i1, c.end, rq, rp, x, up, uq, flag, tauq_m, taup_m, tauq, taup,
+                                  ARR ? c.nq : 0);
 }
 
 // One lane's share of a tile: its two pieces.  A bf16 piece is 8 tokens and is filtered on its own; two fp32
 // pieces (or the 8 consecutive tokens of the element-load path) make one group of 8.
-template <int DT, bool VEC, bool HASQ>
+template <int DT, bool VEC, bool HASQ, bool ARR>
 __device__ __forceinline__ void filter_lane(const RaceArgs& a, const Seg& c, Lds& lds, const HotConsts& h, int32_t ia,
                                             int32_t ib, const Raw& rq, const Raw& rp, float& tauq, float& taup) {
     constexpr bool RAWF32 = (DT == ERSD_F32) || !VEC;
@@ -481,15 +576,28 @@ __device__ __forceinline__ void filter_lane(const RaceArgs& a, const Seg& c, Lds
     if (VEC && DT == ERSD_BF16) {
         Raw hq, hp;
         hq.a = rq.a; hq.b = rq.a; hp.a = rp.a; hp.b = rp.a;
-        filter_tile<RAWF32, HASQ>(a, c, lds, h, ia, ia + 4, hq, hp, tauq, taup);
+        filter_tile<RAWF32, HASQ, ARR>(a, c, lds, h, ia, ia + 4, hq, hp, tauq, taup);
         hq.a = rq.b; hq.b = rq.b; hp.a = rp.b; hp.b = rp.b;
-        filter_tile<RAWF32, HASQ>(a, c, lds, h, ib, ib + 4, hq, hp, tauq, taup);
+        filter_tile<RAWF32, HASQ, ARR>(a, c, lds, h, ib, ib + 4, hq, hp, tauq, taup);
     } else {
-        filter_tile<RAWF32, HASQ>(a, c, lds, h, ia, ib, rq, rp, tauq, taup);
+        filter_tile<RAWF32, HASQ, ARR>(a, c, lds, h, ia, ib, rq, rp, tauq, taup);
     }
 }
 
-template <int DT, bool VEC, bool HASQ>
+// The n-th largest of the wavefront's 128 values (two per lane; kTauInit stands for "none"), by n rounds of
+// maximum and knock-out.  All lanes of the wavefront call this.
+__device__ __forceinline__ float wave_nth_largest(float v0, float v1, int32_t n) {
+    float hi = fmaxf(v0, v1), lo = fminf(v0, v1), m = kTauInit;
+    const int lane = threadIdx.x & (kWave - 1);
+    for (int32_t r = 0; r < n; ++r) {
+        m = wave_max(hi);
+        const uint64_t holders = __builtin_amdgcn_ballot_w64(hi == m);
+        if (lane == __builtin_ctzll(holders)) { hi = lo; lo = kTauInit; }
+    }
+    return m;
+}
+
+template <int DT, bool VEC, bool HASQ, bool ARR>
 __device__ void filter_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
     constexpr bool RAWF32 = (DT == ERSD_F32) || !VEC;
     typedef TileShape<DT, VEC> TS;
@@ -517,6 +625,7 @@ __device__ void filter_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
     {
         uint32_t w[4];
         philox4x32((uint32_t)first >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, w);
+        float bq[2] = {kTauInit, kTauInit};
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
             if (first + e < c.end) {
@@ -525,12 +634,15 @@ __device__ void filter_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
                 if (sp > -INFINITY) taup = fmaxf(taup, sp - refine_err(sp));
                 if (HASQ) {
                     const float sq = fmaf(raw_logit<RAWF32>(qa, e), c2, -l2e);
-                    if (sq > -INFINITY) tauq = fmaxf(tauq, sq - refine_err(sq));
+                    if (sq > -INFINITY) bq[e] = fmaxf(kTauInit, sq - refine_err(sq));
                 }
             }
         }
         taup = wave_max(taup);
-        if (HASQ) tauq = wave_max(tauq);
+        // draft side: the largest bound, or (arrival trees) the nq-th largest of this wavefront's sample, which is
+        // below the nq-th largest score of the segment.  These tokens are not entered into lds.top: the stream
+        // meets them again.
+        if (HASQ) tauq = ARR && c.nq > 1 ? wave_nth_largest(bq[0], bq[1], c.nq) : wave_max(fmaxf(bq[0], bq[1]));
         if ((tid & (kWave - 1)) == 0) {
             lds_tau_raise(lds, 1, taup);
             if (HASQ) lds_tau_raise(lds, 0, tauq);
@@ -549,7 +661,7 @@ __device__ void filter_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
                 const int32_t nt = base + (st + kAhead) * kTile, ct = base + st * kTile;
                 pr[nb] = load_raw<DT, VEC>(c.prow, TS::piece_a(nt, tid), TS::piece_b(nt, tid), c.end);
                 if (HASQ) q[nb] = load_raw<DT, VEC>(c.qrow, TS::piece_a(nt, tid), TS::piece_b(nt, tid), c.end);
-                filter_lane<DT, VEC, HASQ>(a, c, lds, h, TS::piece_a(ct, tid), TS::piece_b(ct, tid), q[st], pr[st],
+                filter_lane<DT, VEC, HASQ, ARR>(a, c, lds, h, TS::piece_a(ct, tid), TS::piece_b(ct, tid), q[st], pr[st],
                                            tauq, taup);
                 done = base + (st + 1) * kTile >= c.end;  // workgroup-uniform
             }
@@ -573,8 +685,8 @@ __device__ void race_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
     }
     __syncthreads();
     if (!a.exhaustive) {
-        if (c.qrow) filter_segment<DT, VEC, true>(a, c, lds);
-        else filter_segment<DT, VEC, false>(a, c, lds);
+        if (c.qrow) filter_segment<DT, VEC, true, false>(a, c, lds);
+        else filter_segment<DT, VEC, false, false>(a, c, lds);
     }
     __syncthreads();
 
@@ -682,6 +794,7 @@ race_kernel(RaceArgs a) {
         c.c1 = a.pos0 + j;
         c.c2 = prompt;
         c.c3 = d;
+        c.nq = 0;
         c.begin = (int32_t)(g0 * 8);
         const int64_t e = (int64_t)g1 * 8;
         c.end = e < a.V ? (int32_t)e : a.V;
@@ -696,6 +809,356 @@ race_kernel(RaceArgs a) {
             ++seq;
             if (++d == (uint32_t)a.m) { d = 0; ++prompt; }
         }
+    }
+}
+
+// ------------------------------------------------------------------------------------------ arrival trees
+// Algorithm 5: every context has one race; its children are the first arrivals under the draft model.  A segment
+// of a draft row hands on every token that can be among the row's first nq arrivals (usually nq of them).
+
+// Partition as the device sees it: with a weight table the totals are known on the device only.
+__device__ __forceinline__ Part part_on_device(const Part& in) {
+    Part p = in;
+    if (p.wprefix) {
+        p.Us = (uint64_t)p.wprefix[p.kt] * p.V8;
+        p.U = p.Us * (p.rows / p.kt);
+    }
+    return p;
+}
+
+template <int DT, bool VEC>
+__device__ void race_segment_arr(const RaceArgs& a, const Seg& c, Lds& lds) {
+    const int tid = threadIdx.x;
+    if (tid < 2) {
+        lds.tau[tid] = kTauInit;
+        lds.count[tid] = 0;
+        lds.nsurv[tid] = 0;
+    }
+    if (tid < kMaxRank) lds.top[tid] = kTauInit;
+    if (tid == 0) lds.rounds = 0;
+    __syncthreads();
+    if (!a.exhaustive) {
+        if (c.qrow) filter_segment<DT, VEC, true, true>(a, c, lds);
+        else filter_segment<DT, VEC, false, true>(a, c, lds);
+    }
+    __syncthreads();
+
+    // Wavefronts 0-1 take the draft side, 2-3 the target side.
+    const int side = tid / (kThreads / 2);
+    const int half_tid = tid % (kThreads / 2);
+    const char* row = side == 0 ? c.qrow : c.prow;
+    const int32_t n = row ? lds.count[side] : 0;
+    const bool listed = row && !a.exhaustive && n <= kListCap;
+    const int32_t cap = side == 0 ? kMaxArrSurvivors : kMaxSurvivors;
+    if (listed) {  // keep the candidates whose interval still reaches the final lower bound
+        const float tau = lds_tau(lds, side);
+        for (int32_t t = half_tid; t < n; t += kThreads / 2) {
+            const float s2 = score2(lds.logit[side][t], lds.word[side][t], a.c2);
+            if (s2 + refine_err(s2) >= tau) {
+                const int32_t k = atomicAdd(&lds.nsurv[side], 1);
+                if (k < cap) lds.surv[side][k] = t;
+            }
+        }
+    }
+    __syncthreads();
+    int32_t* out_count = nullptr;
+    Cand* out_rec = nullptr;
+    if (row) {
+        if (side == 0) {
+            SegOutArr* o = a.outq + c.row * a.part.nslot + c.slot;
+            out_count = &o->count;
+            out_rec = o->c;
+        } else {
+            SegOut* o = a.out + (c.row * 2 + 1) * a.part.nslot + c.slot;
+            out_count = &o->count;
+            out_rec = o->c;
+        }
+    }
+    const int32_t ns = lds.nsurv[side];
+    const bool common = listed && ns <= cap;
+    // Rare: too many survivors, an overflowed list, or the reference mode.  Then the wanted arrivals of the segment
+    // are selected exactly, one per round: the best fp64 score among the tokens after the previous pick.
+    const int32_t my_rounds = (row && !common) ? (side == 0 ? c.nq : 1) : 0;
+    if (half_tid == 0 && my_rounds > 0) atomicMax(&lds.rounds, my_rounds);
+    if (common) {
+        if (half_tid == 0) *out_count = ns;
+        if (half_tid < ns) {
+            const int32_t t = lds.surv[side][half_tid];
+            Cand k;
+            k.idx = lds.idx[side][t];
+            k.word = lds.word[side][t];
+            k.logit = lds.logit[side][t];
+            k.s2 = score2(k.logit, k.word, a.c2);
+            out_rec[half_tid] = k;
+        }
+    }
+    __syncthreads();
+    const int32_t rounds = lds.rounds;  // workgroup-uniform
+    const bool from_list = !(a.exhaustive || n > kListCap);
+    double ps = 0.0;
+    int32_t pi = -1, picked = 0;
+    bool alive = my_rounds > 0;
+    for (int32_t r = 0; r < rounds; ++r) {
+        const bool mine = alive && r < my_rounds;
+        double bs = -INFINITY;
+        int32_t bi = -1;
+        if (mine) {
+            if (from_list) {
+                for (int32_t t = half_tid; t < n; t += kThreads / 2) {
+                    const int32_t i = lds.idx[side][t];
+                    const double sc = exact_score(lds.logit[side][t], a.T, lds.word[side][t]);
+                    if (!(sc > -INFINITY) || (r > 0 && !arrives_after(sc, i, ps, pi))) continue;
+                    if (bi < 0 || better(sc, i, bs, bi)) { bs = sc; bi = i; }
+                }
+            } else {
+                exhaustive_half_after<DT>(a, c, row, half_tid, r > 0, ps, pi, bs, bi);
+            }
+            wave_argmax(bs, bi);
+            if ((tid & (kWave - 1)) == 0) { lds.red_s[tid / kWave] = bs; lds.red_i[tid / kWave] = bi; }
+        }
+        __syncthreads();
+        if (mine) {  // every thread of the half combines its side's wavefronts the same way
+            const int w0 = side * (kWaves / 2);
+            bs = lds.red_s[w0];
+            bi = lds.red_i[w0];
+            for (int w = w0 + 1; w < w0 + kWaves / 2; ++w) {
+                const double os = lds.red_s[w];
+                const int32_t oi = lds.red_i[w];
+                if (oi >= 0 && (bi < 0 || better(os, oi, bs, bi))) { bs = os; bi = oi; }
+            }
+            if (bi < 0) {
+                alive = false;  // no further token with a finite score
+            } else {
+                ps = bs;
+                pi = bi;
+                if (half_tid == 0) {
+                    uint32_t w[4];
+                    philox4x32((uint32_t)bi >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, w);
+                    Cand k;
+                    k.idx = bi;
+                    k.word = w[bi & 3];
+                    k.logit = widen_elem(row, DT, bi);
+                    k.s2 = score2(k.logit, k.word, a.c2);
+                    out_rec[picked] = k;
+                }
+                ++picked;
+            }
+        }
+        __syncthreads();
+    }
+    if (my_rounds > 0 && half_tid == 0) *out_count = picked;
+}
+
+template <int DT, bool VEC>
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ERSD_WAVES_PER_EU, 8)))
+race_arrivals_kernel(RaceArgs a) {
+    __shared__ Lds lds;
+    const Part p = part_on_device(a.part);
+    uint64_t pos = part_start_pos(p, blockIdx.x);
+    const uint64_t pos_end = part_start_pos(p, blockIdx.x + 1);
+    const size_t es = DT == ERSD_F32 ? 4 : 2;
+    if (pos >= pos_end) return;
+    uint64_t row = pos / p.V8;
+    uint32_t g0 = (uint32_t)(pos - row * p.V8);
+    uint64_t seq = row / p.kt;
+    uint32_t j = (uint32_t)(row - seq * p.kt);  // context
+    while (pos < pos_end) {  // one row segment per trip (workgroup-uniform)
+        Seg c;
+        c.row = row;
+        const uint64_t left = pos_end - pos;
+        const uint32_t g1 = left < (uint64_t)(p.V8 - g0) ? g0 + (uint32_t)left : p.V8;
+        c.nq = a.need[j];
+        c.prow = a.target + (size_t)row * (size_t)a.V * es;
+        c.qrow = c.nq > 0 ? a.draft + (size_t)row * (size_t)a.V * es : nullptr;
+        c.c1 = j;
+        c.c2 = (uint32_t)seq;
+        c.c3 = 0;
+        c.begin = (int32_t)(g0 * 8);
+        const int64_t e = (int64_t)g1 * 8;
+        c.end = e < a.V ? (int32_t)e : a.V;
+        c.slot = g0 == 0 ? 0 : blockIdx.x - part_first_block(p, row);
+        race_segment_arr<DT, VEC>(a, c, lds);
+        pos += g1 - g0;
+        g0 = 0;
+        ++row;
+        if (++j == p.kt) { j = 0; ++seq; }
+    }
+}
+
+// Shape of a (parent, rank) tree, computed once per call by one workgroup: valid[N], need[C] (arrivals wanted per
+// context), wprefix[C + 1] (partition weights), C = N + 1.
+struct ArrMeta {
+    int32_t* valid;
+    int32_t* need;
+    uint32_t* wprefix;
+};
+
+__global__ void __launch_bounds__(kThreads) arrival_meta_kernel(const int32_t* parent, const int32_t* rank, int32_t N,
+                                                                ArrMeta m) {
+    const int tid = threadIdx.x;
+    const int32_t C = N + 1;
+    // 1. a node's own entries are in range and no earlier sibling in range asks for the same arrival
+    for (int32_t n = tid; n < N; n += kThreads) {
+        const int32_t pa = parent[n], rk = rank[n];
+        bool ok = pa >= -1 && pa < n && rk >= 0 && rk < kMaxRank;
+        for (int32_t o = 0; ok && o < n; ++o) {
+            const int32_t po = parent[o], ro = rank[o];
+            if (po == pa && ro == rk && po >= -1 && po < o) ok = false;
+        }
+        m.valid[n] = ok ? 1 : 0;
+    }
+    for (int32_t c = tid; c < C; c += kThreads) m.need[c] = 0;
+    __syncthreads();
+    // 2. ... and the same holds for every ancestor (parent < node bounds the walk)
+    for (int32_t n = tid; n < N; n += kThreads) {
+        bool ok = m.valid[n] != 0;
+        int32_t cur = n;
+        while (ok) {
+            const int32_t pa = parent[cur];
+            if (pa == -1) break;
+            ok = m.valid[pa] != 0;  // own-entry flag of the ancestor (written in step 1, read-only here)
+            cur = pa;
+        }
+        if (ok) atomicMax(&m.need[parent[n] + 1], rank[n] + 1);
+        else if (m.valid[n]) m.valid[n] = 2;  // own entries fine, an ancestor is not: resolved after the barrier
+    }
+    __syncthreads();
+    for (int32_t n = tid; n < N; n += kThreads)
+        if (m.valid[n] == 2) m.valid[n] = 0;
+    // 3. weights: a context with a draft row costs as a pair row
+    __shared__ uint32_t part_sum[kThreads];
+    const int32_t per = (C + kThreads - 1) / kThreads;
+    const int32_t c0 = tid * per, c1 = c0 + per < C ? c0 + per : C;
+    __syncthreads();
+    uint32_t sum = 0;
+    for (int32_t c = c0; c < c1; ++c) sum += m.need[c] > 0 ? kWPair : kWSingle;
+    part_sum[tid] = sum;
+    __syncthreads();
+    uint32_t before = 0;
+    for (int t = 0; t < tid; ++t) before += part_sum[t];
+    for (int32_t c = c0; c < c1; ++c) {
+        m.wprefix[c] = before;
+        before += m.need[c] > 0 ? kWPair : kWSingle;
+    }
+    if (c1 == C && c0 < C) m.wprefix[C] = before;
+}
+
+struct ArrFinishArgs {
+    const SegOutArr* outq;
+    Part part;
+    double T;
+    ArrMeta meta;
+    int32_t* arrivals;       // [B, C, kMaxRank]
+    const int32_t* parent;
+    const int32_t* rank;
+    int32_t N;
+    int32_t* draft_tokens;   // [B, N]
+    const int32_t* target_tokens;  // [B, C]
+    int32_t* accept_len;
+    int32_t* accept_node;
+    int32_t* emitted;        // [B, C]
+};
+
+// The first need[c] arrivals of every draft row from what its segments handed on: one wavefront per row scores
+// the candidates in fp64 and picks them off in order (score descending, index ascending).
+__global__ void __launch_bounds__(kThreads) resolve_arrivals_kernel(ArrFinishArgs f) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const Part p = part_on_device(f.part);
+    const uint64_t row = (uint64_t)blockIdx.x * kWaves + threadIdx.x / kWave;
+    if (row >= p.rows) return;  // whole wavefront
+    const int32_t nq = f.meta.need[row % p.kt];
+    int32_t* arr = f.arrivals + row * kMaxRank;
+    if (nq == 0) {
+        if (lane < kMaxRank) arr[lane] = -1;
+        return;
+    }
+    const uint32_t nsl = part_last_block(p, row) - part_first_block(p, row) + 1;
+    const SegOutArr* o = f.outq + row * p.nslot;
+    const uint32_t total = nsl * kMaxArrSurvivors;
+    constexpr int kKeep = 4;  // scores kept in registers per lane; a row with more candidates recomputes the rest
+    double sc[kKeep];
+    int32_t id[kKeep];
+#pragma unroll
+    for (int k = 0; k < kKeep; ++k) {
+        const uint32_t t = lane + k * kWave;
+        id[k] = -1;
+        sc[k] = 0.0;
+        if (t < total) {
+            const SegOutArr& so = o[t / kMaxArrSurvivors];
+            const int32_t e = (int32_t)(t % kMaxArrSurvivors);
+            if (e < so.count) {
+                id[k] = so.c[e].idx;
+                sc[k] = exact_score(so.c[e].logit, f.T, so.c[e].word);
+            }
+        }
+    }
+    double ps = 0.0;
+    int32_t pi = -1;
+    for (int32_t r = 0; r < kMaxRank; ++r) {  // uniform trip count: the lanes meet in shuffles
+        double bs = -INFINITY;
+        int32_t bi = -1;
+        if (r < nq) {
+#pragma unroll
+            for (int k = 0; k < kKeep; ++k)
+                if (id[k] >= 0 && sc[k] > -INFINITY && (r == 0 || arrives_after(sc[k], id[k], ps, pi)) &&
+                    (bi < 0 || better(sc[k], id[k], bs, bi))) {
+                    bs = sc[k];
+                    bi = id[k];
+                }
+            for (uint32_t t = lane + kKeep * kWave; t < total; t += kWave) {
+                const SegOutArr& so = o[t / kMaxArrSurvivors];
+                const int32_t e = (int32_t)(t % kMaxArrSurvivors);
+                if (e < so.count) {
+                    const double v = exact_score(so.c[e].logit, f.T, so.c[e].word);
+                    const int32_t i = so.c[e].idx;
+                    if (v > -INFINITY && (r == 0 || arrives_after(v, i, ps, pi)) && (bi < 0 || better(v, i, bs, bi))) {
+                        bs = v;
+                        bi = i;
+                    }
+                }
+            }
+        }
+        wave_argmax(bs, bi);
+        if (lane == 0) arr[r] = r < nq ? bi : -1;  // -1: fewer tokens with a finite score than arrivals wanted
+        if (bi >= 0) { ps = bs; pi = bi; }
+        else ps = -INFINITY, pi = 0x7fffffff;      // nothing is left after this
+    }
+}
+
+// Per prompt: the drafted token of every node, then the verification walk of Algorithm 5.
+__global__ void __launch_bounds__(kThreads) arrival_walk_kernel(ArrFinishArgs f) {
+    const int tid = threadIdx.x;
+    const int32_t b = blockIdx.x, N = f.N, C = N + 1;
+    int32_t* dtok = f.draft_tokens + (int64_t)b * N;
+    const int32_t* ttok = f.target_tokens + (int64_t)b * C;
+    int32_t* emitted = f.emitted + (int64_t)b * C;
+    for (int32_t n = tid; n < N; n += kThreads)
+        dtok[n] = f.meta.valid[n] ? f.arrivals[((int64_t)b * C + f.parent[n] + 1) * kMaxRank + f.rank[n]] : -1;
+    for (int32_t c = tid; c < C; c += kThreads) emitted[c] = -1;
+    __shared__ int32_t match;
+    if (tid == 0) match = 0x7fffffff;
+    __syncthreads();  // this workgroup's writes to dtok are re-read below
+    int32_t ctx = 0, len = 0, node = -1;
+    while (true) {  // the context index grows with every step, so at most C trips
+        const int32_t t = ttok[ctx];
+        for (int32_t n = tid; n < N; n += kThreads)
+            if (f.meta.valid[n] && f.parent[n] + 1 == ctx && dtok[n] == t) atomicMin(&match, n);
+        __syncthreads();
+        const int32_t next = match;
+        __syncthreads();
+        if (tid == 0) {
+            emitted[len] = t;
+            match = 0x7fffffff;
+        }
+        __syncthreads();
+        if (next == 0x7fffffff) break;
+        ++len;
+        node = next;
+        ctx = next + 1;
+    }
+    if (tid == 0) {
+        f.accept_len[b] = len;
+        f.accept_node[b] = node;
     }
 }
 
@@ -785,7 +1248,7 @@ __device__ int32_t resolve_row(const SegOut* o, uint32_t nslots, double T, bool 
 // Tokens: every (row, side) pair is resolved by eight lanes; 32 pairs per workgroup.
 __global__ void __launch_bounds__(kThreads) resolve_kernel(FinishArgs f) {
     const int tid = threadIdx.x;
-    const Part& p = f.part;
+    const Part p = part_on_device(f.part);
     const uint64_t item = (uint64_t)blockIdx.x * (kThreads / 8) + (tid >> 3);
     const uint64_t row = item >> 1;
     const int side = (int)(item & 1);
@@ -969,6 +1432,7 @@ Part make_part(const Geometry& g, uint32_t blocks) {
     p.kd = (uint32_t)g.kd;
     p.kt = (uint32_t)g.kt;
     p.rows = (uint64_t)g.B * g.m * g.kt;
+    p.wprefix = nullptr;
     p.pair_units = (uint64_t)kWPair * p.kd * p.V8;
     p.Us = p.pair_units + (uint64_t)kWSingle * (p.kt - p.kd) * p.V8;
     p.U = p.Us * (uint64_t)g.B * g.m;
@@ -1103,9 +1567,183 @@ int launch(const void* dl, const void* tl, ersd_dtype dt, const Geometry& g, flo
                          stream);
 }
 
+// ---- arrival trees: sizes, workspace layout, launches
+bool arrival_sizes_ok(int32_t B, int32_t N, int32_t V) {
+    if (N < 1 || N > kMaxArrNodes) return false;
+    return sizes_ok(B, 1, N + 1, N + 1, V);
+}
+
+uint32_t arrival_nslot(int32_t B, int32_t C, uint32_t G) {
+    // a row has at most kWPair * V8 cost units and a share at least kWSingle * V8 * B * C / G of them
+    return (uint32_t)(((uint64_t)kWPair * G) / ((uint64_t)kWSingle * B * C)) + 2;
+}
+
+uint32_t arrival_blocks(int32_t B, int32_t C, int32_t V, uint32_t blocks) {
+    const uint64_t v8 = ((uint64_t)V + 7) / 8;
+    uint64_t G = blocks;
+    const uint64_t by_quota = (uint64_t)kWSingle * v8 * B * C / kMinQuota;
+    if (G > by_quota) G = by_quota;
+    return G < 1 ? 1u : (uint32_t)G;
+}
+
+struct ArrLayout {
+    size_t out, outq, arrivals, valid, need, wprefix, total;
+};
+
+size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
+
+ArrLayout arrival_layout(int32_t B, int32_t N, int32_t V) {
+    const int32_t C = N + 1;
+    const uint64_t rows = (uint64_t)B * C;
+    const uint32_t nslot = arrival_nslot(B, C, arrival_blocks(B, C, V, kMaxBlocks));  // the most any launch uses
+    ArrLayout l;
+    l.out = 0;
+    l.outq = align16(l.out + rows * 2 * nslot * sizeof(SegOut));
+    l.arrivals = align16(l.outq + rows * nslot * sizeof(SegOutArr));
+    l.valid = align16(l.arrivals + rows * kMaxRank * sizeof(int32_t));
+    l.need = align16(l.valid + (size_t)N * sizeof(int32_t));
+    l.wprefix = align16(l.need + (size_t)C * sizeof(int32_t));
+    l.total = align16(l.wprefix + (size_t)(C + 1) * sizeof(uint32_t));
+    return l;
+}
+
+int arrival_race_blocks(ersd_dtype dt, bool vec) {
+    static std::atomic<int> cache[4];
+    const int forced = env_int("ERSD_FORCE_BLOCKS", 0);  // tests only
+    if (forced > 0) return forced > (int)kMaxBlocks ? (int)kMaxBlocks : forced;
+    if (dt == ERSD_F32) return vec ? resident_blocks(race_arrivals_kernel<ERSD_F32, true>, cache[0])
+                                   : resident_blocks(race_arrivals_kernel<ERSD_F32, false>, cache[1]);
+    return vec ? resident_blocks(race_arrivals_kernel<ERSD_BF16, true>, cache[2])
+               : resident_blocks(race_arrivals_kernel<ERSD_BF16, false>, cache[3]);
+}
+
+int launch_arrival_tree(const void* dl, const void* tl, ersd_dtype dt, int32_t B, int32_t N, int32_t V,
+                        const int32_t* parent, const int32_t* rank, float T, uint64_t seed, int32_t* dtok,
+                        int32_t* ttok, int32_t* acc, int32_t* accept_node, int32_t* emitted, void* ws, void* stream) {
+    const int32_t C = N + 1;
+    const bool vec = (V % 8) == 0;
+    const int blocks = arrival_race_blocks(dt, vec);
+    if (blocks < 1) return ERSD_ERR_HIP;
+    const ArrLayout l = arrival_layout(B, N, V);
+    char* base = static_cast<char*>(ws);
+    ArrMeta meta;
+    meta.valid = reinterpret_cast<int32_t*>(base + l.valid);
+    meta.need = reinterpret_cast<int32_t*>(base + l.need);
+    meta.wprefix = reinterpret_cast<uint32_t*>(base + l.wprefix);
+
+    Part p;
+    p.V8 = (uint32_t)(((int64_t)V + 7) / 8);
+    p.kd = 0;                    // no closed-form pair rows: the table decides
+    p.kt = (uint32_t)C;
+    p.rows = (uint64_t)B * C;
+    p.pair_units = 0;
+    p.Us = 0;                    // filled in on the device from the table
+    p.U = 0;
+    p.G = arrival_blocks(B, C, V, (uint32_t)blocks);
+    p.nslot = arrival_nslot(B, C, p.G);
+    p.wprefix = meta.wprefix;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(arrival_meta_kernel, dim3(1), dim3(kThreads), 0, s, parent, rank, N, meta);
+
+    RaceArgs a;
+    a.draft = static_cast<const char*>(dl);
+    a.target = static_cast<const char*>(tl);
+    a.out = reinterpret_cast<SegOut*>(base + l.out);
+    a.outq = reinterpret_cast<SegOutArr*>(base + l.outq);
+    a.need = meta.need;
+    a.part = p;
+    a.V = V;
+    a.m = 1;
+    a.pos0 = 0;
+    a.key0 = (uint32_t)(seed & 0xffffffffu);
+    a.key1 = (uint32_t)(seed >> 32);
+    a.T = (double)T;
+    a.c2 = (float)(1.4426950408889634 / (double)T);
+    const char* mode = std::getenv("ERSD_KERNEL");  // tests only
+    a.exhaustive = mode && std::strcmp(mode, "exhaustive") == 0;
+    const dim3 grid(p.G), block(kThreads);
+    if (dt == ERSD_F32) {
+        if (vec) hipLaunchKernelGGL((race_arrivals_kernel<ERSD_F32, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((race_arrivals_kernel<ERSD_F32, false>), grid, block, 0, s, a);
+    } else {
+        if (vec) hipLaunchKernelGGL((race_arrivals_kernel<ERSD_BF16, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((race_arrivals_kernel<ERSD_BF16, false>), grid, block, 0, s, a);
+    }
+
+    FinishArgs f;  // winners under the target model, by the kernel the other variants use (draft side switched off)
+    f.out = a.out;
+    f.T = (double)T;
+    f.part = p;
+    f.m = 1;
+    f.variant = -1;
+    f.parent = nullptr;
+    f.draft_tokens = nullptr;
+    f.target_tokens = ttok;
+    f.accept_len = nullptr;
+    f.best_draft = nullptr;
+    f.best_len = nullptr;
+    f.accept_node = nullptr;
+    const uint64_t items = p.rows * 2;
+    hipLaunchKernelGGL(resolve_kernel, dim3((uint32_t)((items + kThreads / 8 - 1) / (kThreads / 8))), dim3(kThreads), 0,
+                       s, f);
+
+    ArrFinishArgs af;
+    af.outq = a.outq;
+    af.part = p;
+    af.T = (double)T;
+    af.meta = meta;
+    af.arrivals = reinterpret_cast<int32_t*>(base + l.arrivals);
+    af.parent = parent;
+    af.rank = rank;
+    af.N = N;
+    af.draft_tokens = dtok;
+    af.target_tokens = ttok;
+    af.accept_len = acc;
+    af.accept_node = accept_node;
+    af.emitted = emitted;
+    hipLaunchKernelGGL(resolve_arrivals_kernel, dim3((uint32_t)((p.rows + kWaves - 1) / kWaves)), dim3(kThreads), 0, s,
+                       af);
+    hipLaunchKernelGGL(arrival_walk_kernel, dim3((uint32_t)B), dim3(kThreads), 0, s, af);
+    return hipGetLastError() == hipSuccess ? ERSD_OK : ERSD_ERR_HIP;
+}
+
 }  // namespace
 
 extern "C" {
+
+size_t ersd_race_arrival_tree_workspace_bytes(int32_t B, int32_t N, int32_t V, ersd_dtype dt) {
+    if (dt != ERSD_F32 && dt != ERSD_BF16) return 0;
+    if (!arrival_sizes_ok(B, N, V)) return 0;
+    return arrival_layout(B, N, V).total;
+}
+
+int ersd_race_verify_arrival_tree(const void* draft_logits, const void* target_logits, ersd_dtype dt, int32_t B,
+                                  int32_t N, int32_t V, const int32_t* parent, const int32_t* rank, float temperature,
+                                  uint64_t seed, int32_t* draft_tokens, int32_t* target_tokens, int32_t* accept_len,
+                                  int32_t* accept_node, int32_t* emitted, void* workspace, size_t workspace_bytes,
+                                  void* stream) {
+    if (!parent || !rank || !draft_tokens || !target_tokens || !accept_len || !accept_node || !emitted || !workspace)
+        return ERSD_ERR_NULL_POINTER;
+    const int rc = check_common(draft_logits, target_logits, dt, temperature, workspace);
+    if (rc != ERSD_OK) return rc;
+    if (!arrival_sizes_ok(B, N, V)) return ERSD_ERR_INVALID_ARG;
+    if (workspace_bytes < arrival_layout(B, N, V).total) return ERSD_ERR_WORKSPACE_TOO_SMALL;
+    return launch_arrival_tree(draft_logits, target_logits, dt, B, N, V, parent, rank, temperature, seed, draft_tokens,
+                               target_tokens, accept_len, accept_node, emitted, workspace, stream);
+}
+
+int ersd_arrival_tree_validate_host(const int32_t* parent_host, const int32_t* rank_host, int32_t N) {
+    if (!parent_host || !rank_host || N < 1 || N > kMaxArrNodes) return 0;
+    for (int32_t n = 0; n < N; ++n) {
+        if (parent_host[n] < -1 || parent_host[n] >= n || rank_host[n] < 0 || rank_host[n] >= kMaxRank) return 0;
+        for (int32_t o = 0; o < n; ++o)
+            if (parent_host[o] == parent_host[n] && rank_host[o] == rank_host[n]) return 0;
+    }
+    return 1;
+}
+
+int ersd_max_rank(void) { return kMaxRank; }
 
 size_t ersd_race_workspace_bytes(int variant, int32_t B, int32_t m, int32_t k_or_N, int32_t V, ersd_dtype dt) {
     if (dt != ERSD_F32 && dt != ERSD_BF16) return 0;
@@ -1289,6 +1927,6 @@ const char* ersd_status_string(int status) {
 
 int ersd_philox_rounds(void) { return kPhiloxRounds; }
 
-int ersd_version(void) { return 300; }
+int ersd_version(void) { return 400; }
 
 }  // extern "C"

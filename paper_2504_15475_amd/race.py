@@ -55,6 +55,14 @@ def lib():
         L.ersd_race_sample_workspace_bytes.restype = sz
         L.ersd_accept_lengths.argtypes = [ctypes.c_int, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
         L.ersd_accept_lengths.restype = ctypes.c_int
+        L.ersd_race_verify_arrival_tree.argtypes = [vp, vp, ctypes.c_int, i32, i32, i32, vp, vp, f32, u64,
+                                                    vp, vp, vp, vp, vp, vp, sz, vp]
+        L.ersd_race_verify_arrival_tree.restype = ctypes.c_int
+        L.ersd_race_arrival_tree_workspace_bytes.argtypes = [i32, i32, i32, ctypes.c_int]
+        L.ersd_race_arrival_tree_workspace_bytes.restype = sz
+        L.ersd_arrival_tree_validate_host.argtypes = [vp, vp, i32]
+        L.ersd_arrival_tree_validate_host.restype = ctypes.c_int
+        L.ersd_max_rank.restype = ctypes.c_int
         L.ersd_selftest_bounds.argtypes = [vp, vp]
         L.ersd_selftest_bounds.restype = ctypes.c_int
         L.ersd_tree_validate_host.argtypes = [vp, i32]
@@ -334,3 +342,52 @@ def tree_validate_host(parent):
     import numpy as np
     a = np.ascontiguousarray(np.asarray(parent, dtype=np.int32))
     return bool(lib().ersd_tree_validate_host(a.ctypes.data, a.shape[0]))
+
+
+def max_rank():
+    return lib().ersd_max_rank()
+
+
+def arrival_tree_workspace_bytes(B, N, V, dtype_code):
+    return int(lib().ersd_race_arrival_tree_workspace_bytes(B, N, V, dtype_code))
+
+
+def race_verify_arrival_tree(draft_logits, target_logits, parent, rank, temperature, seed, workspace=None):
+    """Algorithm 5.  draft, target [B,N+1,V] (one row per context); parent, rank int32 [N] on the GPU.
+
+    -> (draft_tokens [B,N], target_tokens [B,N+1], accept_len [B], accept_node [B], emitted [B,N+1])
+    """
+    d, t = _dev(draft_logits, "draft_logits"), _dev(target_logits, "target_logits")
+    par, rk = _dev(parent, "parent"), _dev(rank, "rank")
+    code = _dtype_code(d)
+    if _dtype_code(t) != code:
+        raise TypeError("draft and target logits must share a dtype")
+    B, C, V = d.shape
+    N = C - 1
+    if tuple(t.shape) != (B, C, V):
+        raise ValueError(f"target_logits must be [B,N+1,V]=({B},{C},{V}), got {tuple(t.shape)}")
+    if par.dtype != torch.int32 or rk.dtype != torch.int32 or tuple(par.shape) != (N,) or tuple(rk.shape) != (N,):
+        raise ValueError("parent and rank must be int32 [N]")
+    need = arrival_tree_workspace_bytes(B, N, V, code)
+    if need == 0:
+        raise ErsdError(-2, status_string(-2))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=d.device)
+    dtok = torch.empty((B, N), dtype=torch.int32, device=d.device)
+    ttok = torch.empty((B, C), dtype=torch.int32, device=d.device)
+    acc = torch.empty((B,), dtype=torch.int32, device=d.device)
+    node = torch.empty((B,), dtype=torch.int32, device=d.device)
+    emitted = torch.empty((B, C), dtype=torch.int32, device=d.device)
+    _check(lib().ersd_race_verify_arrival_tree(d.data_ptr(), t.data_ptr(), code, B, N, V, par.data_ptr(), rk.data_ptr(),
+                                               float(temperature), int(seed), dtok.data_ptr(), ttok.data_ptr(),
+                                               acc.data_ptr(), node.data_ptr(), emitted.data_ptr(),
+                                               workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                               _stream()))
+    return dtok, ttok, acc, node, emitted
+
+
+def arrival_tree_validate_host(parent, rank):
+    import numpy as np
+    par = np.ascontiguousarray(np.asarray(parent, dtype=np.int32))
+    rk = np.ascontiguousarray(np.asarray(rank, dtype=np.int32))
+    return bool(lib().ersd_arrival_tree_validate_host(par.ctypes.data, rk.ctypes.data, par.shape[0]))

@@ -23,7 +23,7 @@ import torch
 class Workload:
     index: int
     name: str
-    variant: str          # "sequence" | "multi" | "tree"
+    variant: str          # "sequence" | "multi" | "tree" | "arrival_tree"
     B: int
     k: int                # drafted positions per sequence (tree: unused, 0)
     V: int
@@ -39,6 +39,9 @@ class Workload:
         """Logits read by one pass (the unit of the throughput metric)."""
         if self.variant == "tree":
             return self.B * 2 * self.N * self.V
+        if self.variant == "arrival_tree":  # one target row per context, one draft row per context with a child
+            with_child = len(set(int(p) for p in tree_parents(self)))
+            return self.B * (self.N + 1 + with_child) * self.V
         return self.B * self.m * (2 * self.k + 1) * self.V
 
     @property
@@ -61,6 +64,12 @@ WORKLOADS = (
     Workload(4, "tree_B16_N64_V256000_bf16", "tree", B=16, k=0, V=256000, dtype=torch.bfloat16, temperature=1.0,
              seed=4, N=64, level_sizes=(4, 8, 12, 14, 14, 12)),
 )
+
+
+# The tree of workload 4 verified as Algorithm 5 states it: one row per context (N + 1 of them), the children of a
+# context are the first arrivals of its race under the draft model (rank = order among siblings).
+ARRIVAL_TREE = Workload(5, "arrival_tree_B16_N64_V256000_bf16", "arrival_tree", B=16, k=0, V=256000,
+                        dtype=torch.bfloat16, temperature=1.0, seed=4, N=64, level_sizes=(4, 8, 12, 14, 14, 12))
 
 
 def shrink(w: Workload, **kw) -> Workload:
@@ -91,6 +100,16 @@ def tree_parents(w: Workload) -> np.ndarray:
     return parent
 
 
+def sibling_ranks(parent: np.ndarray) -> np.ndarray:
+    """rank[n] = how many earlier nodes share n's parent (children of a context take its arrivals in order)."""
+    seen = {}
+    rank = np.empty(len(parent), dtype=np.int32)
+    for n, p in enumerate(parent):
+        rank[n] = seen.get(int(p), 0)
+        seen[int(p)] = rank[n] + 1
+    return rank
+
+
 def _randn(shape, gen, device, chunk_rows=None):
     return torch.randn(shape, generator=gen, device=device, dtype=torch.float32)
 
@@ -99,7 +118,7 @@ def make_inputs(w: Workload, device="cpu"):
     """-> dict(draft, target[, parent]) of tensors on `device` in the workload dtype.
 
     sequence: draft [B,k,V], target [B,k+1,V];  multi: draft [B,m,k,V], target [B,m,k+1,V];
-    tree: draft, target [B,N,V] and parent int32 [N].
+    tree: draft, target [B,N,V] and parent int32 [N];  arrival_tree: draft, target [B,N+1,V], parent, rank int32 [N].
     """
     dev = torch.device(device)
     gen = torch.Generator(device=dev)
@@ -128,15 +147,23 @@ def make_inputs(w: Workload, device="cpu"):
         N = w.N
         target = 3.0 * _randn((B, N, V), gen, dev)
         draft = target + 0.6 * _randn((B, N, V), gen, dev)
+    elif w.index == 5:
+        C = w.N + 1
+        target = 3.0 * _randn((B, C, V), gen, dev)
+        draft = target + 0.6 * _randn((B, C, V), gen, dev)
     else:
         raise ValueError(w.index)
     out = dict(draft=draft.to(w.dtype).contiguous(), target=target.to(w.dtype).contiguous())
-    if w.variant == "tree":
-        out["parent"] = torch.from_numpy(tree_parents(w)).to(dev)
+    if w.variant in ("tree", "arrival_tree"):
+        par = tree_parents(w)
+        out["parent"] = torch.from_numpy(par).to(dev)
+        if w.variant == "arrival_tree":
+            out["rank"] = torch.from_numpy(sibling_ranks(par)).to(dev)
     return out
 
 
 def describe(w: Workload) -> str:
-    shape = {"sequence": f"B={w.B} k={w.k}", "multi": f"B={w.B} m={w.m} k={w.k}", "tree": f"B={w.B} N={w.N}"}[w.variant]
+    shape = {"sequence": f"B={w.B} k={w.k}", "multi": f"B={w.B} m={w.m} k={w.k}", "tree": f"B={w.B} N={w.N}",
+             "arrival_tree": f"B={w.B} N={w.N}"}[w.variant]
     dt = "fp32" if w.dtype == torch.float32 else "bf16"
     return f"{w.variant} {shape} V={w.V} {dt} T={w.temperature} seed={w.seed}"

@@ -82,3 +82,44 @@ def check_tree(gpu, ora, oracle_mod, draft_host, target_host, parent_host, T, se
     if ex == 0:
         assert np.array_equal(acc, ora["accept_len"]) and np.array_equal(node, ora["accept_node"])
     return ex
+
+
+def arrival_walk_reference(dtok, ttok, parent, valid):
+    """The verification walk on token arrays (host)."""
+    B, N = dtok.shape
+    acc = np.zeros(B, dtype=np.int32)
+    node = np.full(B, -1, dtype=np.int32)
+    emitted = np.full((B, N + 1), -1, dtype=np.int32)
+    for b in range(B):
+        ctx = 0
+        while True:
+            t = ttok[b, ctx]
+            emitted[b, acc[b]] = t
+            nxt = [n for n in range(N) if valid[n] and parent[n] + 1 == ctx and dtok[b, n] == t]
+            if not nxt:
+                break
+            acc[b] += 1
+            node[b] = nxt[0]
+            ctx = nxt[0] + 1
+    return acc, node, emitted
+
+
+def check_arrival_tree(gpu, ora, oracle_mod, target_host, parent_host, rank_host, T, seed, max_rank):
+    """gpu: (draft_tokens, target_tokens, accept_len, accept_node, emitted); ora: oracle dict with infos."""
+    dtok, ttok, acc, node, emitted = (_np(x) for x in gpu)
+    parent_host, rank_host = np.asarray(parent_host), np.asarray(rank_host)
+    valid, need = oracle_mod.arrival_tree_shape(parent_host, rank_host, max_rank)
+    ex = compare_tokens("target", ttok, ora["target_info"], oracle_mod, lambda ix: target_host[ix], T, seed,
+                        lambda ix: (ix[1], ix[0], 0))
+    for b, n in map(tuple, np.argwhere(dtok != ora["draft_tokens"])):
+        ctx = parent_host[n] + 1
+        assert valid[n] and ora["arrival_near_tie"][b, ctx] == 1, (
+            f"draft({b},{n}): gpu {dtok[b, n]} != oracle {ora['draft_tokens'][b, n]} and the arrivals of context "
+            f"{ctx} are not near-tied")
+        ex += 1
+    ra, rn, re = arrival_walk_reference(dtok, ttok, parent_host, valid)
+    assert np.array_equal(acc, ra) and np.array_equal(node, rn) and np.array_equal(emitted, re)
+    if ex == 0:
+        assert np.array_equal(acc, ora["accept_len"]) and np.array_equal(node, ora["accept_node"])
+        assert np.array_equal(emitted, ora["emitted"])
+    return ex
