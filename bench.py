@@ -30,7 +30,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", type=int, default=1, help="index into the five benchmark workloads (default 1)")
+    ap.add_argument("--workload", type=int, default=1,
+                    help="index into the five benchmark workloads (default 1); 5 = the tree of workload 4 verified "
+                         "as Algorithm 5 states it (children of a context = first arrivals of one race)")
     ap.add_argument("--buffers", type=int, default=4, help="distinct input sets rotated through (cache defeat)")
     ap.add_argument("--event-every", type=int, default=8,
                     help="record HIP events around the race kernel of every N-th timed step (events cost a few us)")
@@ -51,6 +53,10 @@ def main():
 
     from paper_2504_15475_amd import race, workloads as wl
     race.lib()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    if args.workload == 5:
+        return bench_arrival_tree(args, wl.ARRIVAL_TREE, dev)
     w = wl.WORKLOADS[args.workload]
     variant = {"sequence": race.VARIANT_SEQUENCE, "multi": race.VARIANT_MULTI, "tree": race.VARIANT_TREE}[w.variant]
     dev = torch.device("cuda:0")
@@ -133,6 +139,72 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"], out["check"] = cpu_baseline(w, base, calls[0], variant)
     print(json.dumps(out), flush=True)
+    return 0
+
+
+def bench_arrival_tree(args, w, dev):
+    """Algorithm 5 tree form (ersd_race_verify_arrival_tree); events bracket the whole call (five kernels)."""
+    from paper_2504_15475_amd import race, workloads as wl
+    base = wl.make_inputs(w, dev)
+    sets = [base]
+    for _ in range(max(1, args.buffers) - 1):
+        sets.append(dict(base, draft=(base["draft"].float() + 0.01 * torch.randn(base["draft"].shape, device=dev))
+                         .to(w.dtype).contiguous(),
+                         target=(base["target"].float() + 0.01 * torch.randn(base["target"].shape, device=dev))
+                         .to(w.dtype).contiguous()))
+    B, C, V = base["draft"].shape
+    code = race._dtype_code(base["draft"])
+    ws = torch.empty(race.arrival_tree_workspace_bytes(B, C - 1, V, code), dtype=torch.uint8, device=dev)
+
+    def step(i):
+        x = sets[i % len(sets)]
+        return race.race_verify_arrival_tree(x["draft"], x["target"], x["parent"], x["rank"], w.temperature, w.seed,
+                                             workspace=ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    K = args.steps
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(K):
+        out = step(i)
+    e1.record()
+    torch.cuda.synchronize()
+    total_s = time.perf_counter() - t0
+    gpu_ms = e0.elapsed_time(e1) / K
+    elements = w.race_elements
+    nbytes = elements * w.elem_bytes
+    line = {
+        "metric": "race_elements_per_sec", "value": elements * K / total_s, "unit": "elements/s", "n_gpus": 1,
+        "steps": K, "warmup": args.warmup, "ms_per_step": total_s * 1e3 / K, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": w.name, "entry": "ersd_race_verify_arrival_tree", "contexts": B * C, "V": V,
+                   "philox_rounds": race.philox_rounds(), "mean_accept_len": float(out[2].float().mean())},
+        "roofline": {"bound": "hbm", "achieved": round(nbytes / (gpu_ms * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": round(nbytes / (gpu_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4), "traffic": None,
+                     "kernel": "whole call (tree shape, races, two resolve kernels, walk)",
+                     "kernel_ms_avg": round(gpu_ms, 5), "algorithmic_bytes_per_launch": nbytes},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import race_verify_arrival_tree, num_threads
+        nb = min(B, 4)
+        d_host, t_host = base["draft"][:nb].cpu(), base["target"][:nb].cpu()
+        par, rk = base["parent"].cpu().numpy(), base["rank"].cpu().numpy()
+        t1 = time.perf_counter()
+        ora = race_verify_arrival_tree(d_host, t_host, par, rk, w.temperature, w.seed, max_rank=race.max_rank())
+        dt = time.perf_counter() - t1
+        got = race.race_verify_arrival_tree(base["draft"], base["target"], base["parent"], base["rank"], w.temperature,
+                                            w.seed, workspace=ws)
+        torch.cuda.synchronize()
+        mism = int((got[0][:nb].cpu().numpy() != ora["draft_tokens"]).sum()
+                   + (got[1][:nb].cpu().numpy() != ora["target_tokens"]).sum()
+                   + (got[2][:nb].cpu().numpy() != ora["accept_len"]).sum())
+        line["cpu_baseline"] = {"value": elements * nb / B / dt, "unit": "elements/s", "cores": num_threads(),
+                                "kind": "oracle", "sample": f"first {nb} of {B} prompts, one pass",
+                                "check": {"mismatches_vs_oracle": mism}}
+    print(json.dumps(line), flush=True)
     return 0
 
 

@@ -997,53 +997,81 @@ __global__ void __launch_bounds__(kThreads) arrival_meta_kernel(const int32_t* p
                                                                 ArrMeta m) {
     const int tid = threadIdx.x;
     const int32_t C = N + 1;
-    // 1. a node's own entries are in range and no earlier sibling in range asks for the same arrival
+    // small trees (the usual case) are read once into LDS; the scans below then run on LDS
+    constexpr int32_t kStaged = 2048;
+    __shared__ int32_t sp[kStaged], sr[kStaged], sv[kStaged];
+    const bool staged = N <= kStaged;
+    if (staged) {
+        for (int32_t n = tid; n < N; n += kThreads) { sp[n] = parent[n]; sr[n] = rank[n]; }
+        __syncthreads();
+    }
+    // 1. own[n]: a node's own entries are in range and no earlier sibling in range asks for the same arrival
     for (int32_t n = tid; n < N; n += kThreads) {
-        const int32_t pa = parent[n], rk = rank[n];
-        bool ok = pa >= -1 && pa < n && rk >= 0 && rk < kMaxRank;
-        for (int32_t o = 0; ok && o < n; ++o) {
-            const int32_t po = parent[o], ro = rank[o];
-            if (po == pa && ro == rk && po >= -1 && po < o) ok = false;
+        const int32_t pa = staged ? sp[n] : parent[n], rk = staged ? sr[n] : rank[n];
+        const bool ok = pa >= -1 && pa < n && rk >= 0 && rk < kMaxRank;
+        bool dup = false;
+        if (ok) {
+            if (staged) {
+                for (int32_t o = 0; o < n; ++o) dup |= sp[o] == pa && sr[o] == rk && sp[o] < o;
+            } else {
+                for (int32_t o = 0; o < n; ++o) {
+                    const int32_t po = parent[o];
+                    dup |= po == pa && rank[o] == rk && po < o;
+                }
+            }
         }
-        m.valid[n] = ok ? 1 : 0;
+        const int32_t own = ok && !dup ? 1 : 0;
+        if (staged) sv[n] = own;
+        else m.valid[n] = own;
     }
     for (int32_t c = tid; c < C; c += kThreads) m.need[c] = 0;
     __syncthreads();
-    // 2. ... and the same holds for every ancestor (parent < node bounds the walk)
+    // 2. valid[n]: own[] holds for the node and every ancestor (parent < node bounds the walk).  The large-tree
+    // path keeps own[] in m.valid and marks "own but not valid" as 2 until every thread has finished reading.
     for (int32_t n = tid; n < N; n += kThreads) {
-        bool ok = m.valid[n] != 0;
+        bool ok = (staged ? sv[n] : m.valid[n]) != 0;
+        const bool own = ok;
         int32_t cur = n;
         while (ok) {
-            const int32_t pa = parent[cur];
+            const int32_t pa = staged ? sp[cur] : parent[cur];
             if (pa == -1) break;
-            ok = m.valid[pa] != 0;  // own-entry flag of the ancestor (written in step 1, read-only here)
+            ok = (staged ? sv[pa] : m.valid[pa]) != 0;
             cur = pa;
         }
-        if (ok) atomicMax(&m.need[parent[n] + 1], rank[n] + 1);
-        else if (m.valid[n]) m.valid[n] = 2;  // own entries fine, an ancestor is not: resolved after the barrier
+        if (ok) atomicMax(&m.need[(staged ? sp[n] : parent[n]) + 1], (staged ? sr[n] : rank[n]) + 1);
+        if (staged) m.valid[n] = ok ? 1 : 0;
+        else if (own && !ok) m.valid[n] = 2;
     }
     __syncthreads();
-    for (int32_t n = tid; n < N; n += kThreads)
-        if (m.valid[n] == 2) m.valid[n] = 0;
+    if (!staged)
+        for (int32_t n = tid; n < N; n += kThreads)
+            if (m.valid[n] == 2) m.valid[n] = 0;
     // 3. weights: a context with a draft row costs as a pair row
     __shared__ uint32_t part_sum[kThreads];
     const int32_t per = (C + kThreads - 1) / kThreads;
     const int32_t c0 = tid * per, c1 = c0 + per < C ? c0 + per : C;
     __syncthreads();
     uint32_t sum = 0;
-    for (int32_t c = c0; c < c1; ++c) sum += m.need[c] > 0 ? kWPair : kWSingle;
+    // need[] was raised with device atomics: read it past the first-level cache
+    auto weight = [&](int32_t c) {
+        return __hip_atomic_load(&m.need[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) > 0 ? kWPair : kWSingle;
+    };
+    for (int32_t c = c0; c < c1; ++c) sum += weight(c);
     part_sum[tid] = sum;
     __syncthreads();
     uint32_t before = 0;
     for (int t = 0; t < tid; ++t) before += part_sum[t];
     for (int32_t c = c0; c < c1; ++c) {
         m.wprefix[c] = before;
-        before += m.need[c] > 0 ? kWPair : kWSingle;
+        before += weight(c);
     }
     if (c1 == C && c0 < C) m.wprefix[C] = before;
 }
 
+__device__ int32_t resolve_row(const SegOut* o, uint32_t nslots, double T, bool active, int lane8);
+
 struct ArrFinishArgs {
+    const SegOut* out;       // target-side survivors
     const SegOutArr* outq;
     Part part;
     double T;
@@ -1053,7 +1081,8 @@ struct ArrFinishArgs {
     const int32_t* rank;
     int32_t N;
     int32_t* draft_tokens;   // [B, N]
-    const int32_t* target_tokens;  // [B, C]
+    int32_t* target_tokens;  // [B, C]
+    uint32_t target_blocks;  // leading workgroups of the resolve kernel that take the target side
     int32_t* accept_len;
     int32_t* accept_node;
     int32_t* emitted;        // [B, C]
@@ -1064,7 +1093,16 @@ struct ArrFinishArgs {
 __global__ void __launch_bounds__(kThreads) resolve_arrivals_kernel(ArrFinishArgs f) {
     const int lane = threadIdx.x & (kWave - 1);
     const Part p = part_on_device(f.part);
-    const uint64_t row = (uint64_t)blockIdx.x * kWaves + threadIdx.x / kWave;
+    if (blockIdx.x < f.target_blocks) {  // winners under the target model: eight lanes per row, as in the other variants
+        const uint64_t trow = (uint64_t)blockIdx.x * (kThreads / 8) + (threadIdx.x >> 3);
+        const bool active = trow < p.rows;
+        const uint64_t r = active ? trow : 0;
+        const uint32_t n = active ? part_last_block(p, r) - part_first_block(p, r) + 1 : 0;
+        const int32_t tok = resolve_row(f.out + (r * 2 + 1) * p.nslot, n, f.T, active, threadIdx.x & 7);
+        if (active && (threadIdx.x & 7) == 0) f.target_tokens[r] = tok;
+        return;
+    }
+    const uint64_t row = (uint64_t)(blockIdx.x - f.target_blocks) * kWaves + threadIdx.x / kWave;
     if (row >= p.rows) return;  // whole wavefront
     const int32_t nq = f.meta.need[row % p.kt];
     int32_t* arr = f.arrivals + row * kMaxRank;
@@ -1671,25 +1709,10 @@ int launch_arrival_tree(const void* dl, const void* tl, ersd_dtype dt, int32_t B
         else hipLaunchKernelGGL((race_arrivals_kernel<ERSD_BF16, false>), grid, block, 0, s, a);
     }
 
-    FinishArgs f;  // winners under the target model, by the kernel the other variants use (draft side switched off)
-    f.out = a.out;
-    f.T = (double)T;
-    f.part = p;
-    f.m = 1;
-    f.variant = -1;
-    f.parent = nullptr;
-    f.draft_tokens = nullptr;
-    f.target_tokens = ttok;
-    f.accept_len = nullptr;
-    f.best_draft = nullptr;
-    f.best_len = nullptr;
-    f.accept_node = nullptr;
-    const uint64_t items = p.rows * 2;
-    hipLaunchKernelGGL(resolve_kernel, dim3((uint32_t)((items + kThreads / 8 - 1) / (kThreads / 8))), dim3(kThreads), 0,
-                       s, f);
-
     ArrFinishArgs af;
+    af.out = a.out;
     af.outq = a.outq;
+    af.target_blocks = (uint32_t)((p.rows + kThreads / 8 - 1) / (kThreads / 8));
     af.part = p;
     af.T = (double)T;
     af.meta = meta;
@@ -1702,8 +1725,8 @@ int launch_arrival_tree(const void* dl, const void* tl, ersd_dtype dt, int32_t B
     af.accept_len = acc;
     af.accept_node = accept_node;
     af.emitted = emitted;
-    hipLaunchKernelGGL(resolve_arrivals_kernel, dim3((uint32_t)((p.rows + kWaves - 1) / kWaves)), dim3(kThreads), 0, s,
-                       af);
+    hipLaunchKernelGGL(resolve_arrivals_kernel,
+                       dim3(af.target_blocks + (uint32_t)((p.rows + kWaves - 1) / kWaves)), dim3(kThreads), 0, s, af);
     hipLaunchKernelGGL(arrival_walk_kernel, dim3((uint32_t)B), dim3(kThreads), 0, s, af);
     return hipGetLastError() == hipSuccess ? ERSD_OK : ERSD_ERR_HIP;
 }
