@@ -1059,8 +1059,13 @@ __global__ void __launch_bounds__(kThreads) arrival_meta_kernel(const int32_t* p
     for (int32_t c = c0; c < c1; ++c) sum += weight(c);
     part_sum[tid] = sum;
     __syncthreads();
-    uint32_t before = 0;
-    for (int t = 0; t < tid; ++t) before += part_sum[t];
+    for (int off = 1; off < kThreads; off <<= 1) {  // inclusive scan of the per-thread sums
+        const uint32_t add = tid >= off ? part_sum[tid - off] : 0;
+        __syncthreads();
+        part_sum[tid] += add;
+        __syncthreads();
+    }
+    uint32_t before = part_sum[tid] - sum;
     for (int32_t c = c0; c < c1; ++c) {
         m.wprefix[c] = before;
         before += weight(c);
