@@ -226,6 +226,32 @@ size_t ersd_race_arrival_tree_workspace_bytes(int32_t B, int32_t N, int32_t V, e
 /* Host helper: 1 if every node of (parent, rank)[0..N) (HOST arrays) is valid by the rule above, else 0. */
 int ersd_arrival_tree_validate_host(const int32_t* parent_host, const int32_t* rank_host, int32_t N);
 
+/*
+ * Optimal drafting tree, Algorithm 3 (Section 4), for a 0-th order acceptance function as in the paper's
+ * experiments (Section 5): R(j_1 .. j_l) = r[j_1] * ... * r[j_l], r[j] = accept_by_rank[j] = probability that the
+ * child holding arrival j of a context is accepted given that its parent was.  Greedy growth from a priority
+ * queue, O(k log k).  All pointers are HOST arrays; no device work.
+ *   accept_by_rank [nr]: values in [0, 1]; the tree is optimal when they do not increase with j (the algorithm
+ *   offers sibling j + 1 only after sibling j was taken); nr = largest number of children of a vertex
+ *   (<= ERSD_MAX_RANK for use with ersd_race_verify_arrival_tree).
+ *   parent, rank [k] out: the k drafted vertices in the order they were taken (so parent[n] < n; -1 = the root),
+ *   in the layout ersd_race_verify_arrival_tree takes.  Equal acceptance values are taken in the order they
+ *   entered the queue.
+ *   node_accept [k] out or NULL: R of every vertex.  expected_accepted out or NULL: their sum, the expected
+ *   number of accepted drafted tokens under the model.
+ * Returns ERSD_OK, ERSD_ERR_NULL_POINTER, or ERSD_ERR_INVALID_ARG (nr < 1, k < 1, a value outside [0, 1]).
+ */
+int ersd_tree_build_optimal_host(const double* accept_by_rank, int32_t nr, int32_t k, int32_t* parent,
+                                 int32_t* rank, double* node_accept, double* expected_accepted);
+
+/*
+ * The fixed tree of the SpecInfer kind used as a comparison strategy in Section 5: `branches` sequences that share
+ * their first `shared` drafted tokens (the paper: 3 sequences, 2 common tokens).  The prefix is a chain of winners;
+ * the branches leave it as arrivals 0 .. branches-1 of the prefix's last context and continue as chains of
+ * winners, growing in turn until k vertices are placed.  parent, rank [k] out (HOST).
+ */
+int ersd_tree_build_specinfer_host(int32_t k, int32_t shared, int32_t branches, int32_t* parent, int32_t* rank);
+
 /* ERSD_MAX_RANK of the loaded library. */
 int ersd_max_rank(void);
 

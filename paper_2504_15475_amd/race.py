@@ -63,6 +63,10 @@ def lib():
         L.ersd_arrival_tree_validate_host.argtypes = [vp, vp, i32]
         L.ersd_arrival_tree_validate_host.restype = ctypes.c_int
         L.ersd_max_rank.restype = ctypes.c_int
+        L.ersd_tree_build_optimal_host.argtypes = [vp, i32, i32, vp, vp, vp, vp]
+        L.ersd_tree_build_optimal_host.restype = ctypes.c_int
+        L.ersd_tree_build_specinfer_host.argtypes = [i32, i32, i32, vp, vp]
+        L.ersd_tree_build_specinfer_host.restype = ctypes.c_int
         L.ersd_selftest_bounds.argtypes = [vp, vp]
         L.ersd_selftest_bounds.restype = ctypes.c_int
         L.ersd_tree_validate_host.argtypes = [vp, i32]
@@ -391,3 +395,27 @@ def arrival_tree_validate_host(parent, rank):
     par = np.ascontiguousarray(np.asarray(parent, dtype=np.int32))
     rk = np.ascontiguousarray(np.asarray(rank, dtype=np.int32))
     return bool(lib().ersd_arrival_tree_validate_host(par.ctypes.data, rk.ctypes.data, par.shape[0]))
+
+
+def tree_build_optimal(accept_by_rank, k):
+    """Algorithm 3 on the host -> (parent [k], rank [k], node_accept [k], expected_accepted); numpy arrays."""
+    import numpy as np
+    r = np.ascontiguousarray(np.asarray(accept_by_rank, dtype=np.float64))
+    k = int(k)
+    parent = np.empty(max(k, 0), dtype=np.int32)
+    rank = np.empty(max(k, 0), dtype=np.int32)
+    acc = np.empty(max(k, 0), dtype=np.float64)
+    total = ctypes.c_double(0.0)
+    _check(lib().ersd_tree_build_optimal_host(r.ctypes.data, r.shape[0], k, parent.ctypes.data, rank.ctypes.data,
+                                              acc.ctypes.data, ctypes.addressof(total)))
+    return parent, rank, acc, total.value
+
+
+def tree_build_specinfer(k, shared=2, branches=3):
+    """The fixed comparison tree of Section 5 -> (parent [k], rank [k]); numpy arrays."""
+    import numpy as np
+    k = int(k)
+    parent = np.empty(max(k, 0), dtype=np.int32)
+    rank = np.empty(max(k, 0), dtype=np.int32)
+    _check(lib().ersd_tree_build_specinfer_host(k, int(shared), int(branches), parent.ctypes.data, rank.ctypes.data))
+    return parent, rank

@@ -139,3 +139,11 @@ def test_full_size_arrival_tree_matches_oracle(race, oracle_mod):
     inp = wl.make_inputs(w, "cuda")
     run(race, oracle_mod, inp["draft"], inp["target"], inp["parent"].cpu().numpy(), inp["rank"].cpu().numpy(),
         w.temperature, w.seed, note="full size")
+
+
+def test_trees_from_the_builders_verify_like_the_oracle(race, oracle_mod):
+    opt_parent, opt_rank, _, _ = race.tree_build_optimal([0.6, 0.2, 0.1, 0.05, 0.02], 40)
+    si_parent, si_rank = race.tree_build_specinfer(20)
+    for parent, rank in ((opt_parent, opt_rank), (si_parent, si_rank)):
+        draft, target = small_inputs(3, len(parent), 32768, torch.bfloat16, 41, noise=0.4)
+        run(race, oracle_mod, draft, target, parent, rank, 1.0, 8, note="builder tree")
