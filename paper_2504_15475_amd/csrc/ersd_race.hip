@@ -46,6 +46,9 @@ constexpr int kThreads = ERSD_THREADS;              // wavefronts per workgroup:
 #ifndef ERSD_STAGES
 #define ERSD_STAGES 2
 #endif
+#ifndef ERSD_ROTATE_PRIO
+#define ERSD_ROTATE_PRIO 2   // step of the priority rotation per tile; 0 switches it off
+#endif
 constexpr int kStages = ERSD_STAGES;                // register buffers per row: kStages - 1 tiles of loads in flight
 constexpr int kListCap = 512;                       // candidate slots per side per workgroup
 constexpr int kWave = 64;
@@ -183,8 +186,14 @@ __device__ __forceinline__ void philox4x32(uint32_t c0, uint32_t c1, uint32_t c2
     for (int r = 0; r < kPhiloxRounds; ++r) {
         const uint64_t p0 = (uint64_t)kPhiloxM0 * c0;
         const uint64_t p1 = (uint64_t)kPhiloxM1 * c2;
-        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n0, n2;
+        if (r >= 2) {  // gfx950's three-input bitwise operation (truth table 0x96 = a ^ b ^ c): one instruction each
+            n0 = __builtin_amdgcn_bitop3_b32((uint32_t)(p1 >> 32), c1, k0, 0x96);
+            n2 = __builtin_amdgcn_bitop3_b32((uint32_t)(p0 >> 32), c3, k1, 0x96);
+        } else {       // in the first two rounds most operands are wavefront-uniform: left to the scalar unit
+            n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+            n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        }
         c1 = (uint32_t)p1;
         c3 = (uint32_t)p0;
         c0 = n0;
@@ -650,12 +659,28 @@ __device__ void filter_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
     }
 
     const HotConsts h = make_hot_consts(a.c2);
+#if ERSD_ROTATE_PRIO
+    // The hardware issues from the oldest wavefront of a SIMD first, so the resident workgroups of a compute unit
+    // would finish one after the other and the last would run alone, too few wavefronts to hide latency.  The
+    // wavefronts of a SIMD therefore take turns at three priority levels, one step per tile, starting from their
+    // slot number within the SIMD (hardware id register, bits 3:0), which differs between them.
+    uint32_t turn = __builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 4);
+#endif
     // kStages tiles per trip; buffer indices are compile-time constants, so the ring stays in registers
     for (int32_t base = c.begin; base < c.end; base += kStages * kTile) {
         bool done = false;
 #pragma unroll
         for (int st = 0; st < kStages; ++st) {
             if (!done) {
+#if ERSD_ROTATE_PRIO
+                {
+                    const uint32_t pr3 = turn % 3;
+                    if (pr3 == 0) __builtin_amdgcn_s_setprio(0);
+                    else if (pr3 == 1) __builtin_amdgcn_s_setprio(1);
+                    else __builtin_amdgcn_s_setprio(2);
+                    turn += (ERSD_ROTATE_PRIO);
+                }
+#endif
                 constexpr int kAhead = kStages - 1;
                 const int nb = (st + kAhead) % kStages;  // buffer of the tile kAhead tiles ahead
                 const int32_t nt = base + (st + kAhead) * kTile, ct = base + st * kTile;
@@ -667,6 +692,9 @@ __device__ void filter_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
             }
         }
     }
+#if ERSD_ROTATE_PRIO
+    __builtin_amdgcn_s_setprio(0);
+#endif
 }
 
 // fp32 score of a (logit, word) record, exactly as the refine step computes it
