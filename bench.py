@@ -22,7 +22,7 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per race-kernel launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a copy
 # kernel of known size; filled in from the summaries under profiles/ (None = not measured for that workload).
-MEASURED_TRAFFIC_BYTES = {1: 285692987, 2: 5159844663, 3: 1118437597, 4: 1067973628}
+MEASURED_TRAFFIC_BYTES = {1: 286144209, 2: 5171326896, 3: 1119049328, 4: 1068198315}
 
 
 def main():
