@@ -102,10 +102,26 @@ struct Part {
     uint32_t kd, kt;      // draft rows / target rows per sequence
     uint32_t G;           // workgroups
     uint32_t nslot;       // partial slots per (row, side)
+    // Every workgroup works out its share before its first load, and integer division is a long instruction
+    // sequence on this hardware.  When all cost units fit in 32 bits (fast != 0) the quotients below are taken by
+    // multiplication with reciprocals prepared on the host (see magic_of); otherwise by plain 64-bit division.
+    uint32_t fast;
+    uint32_t q, r;        // U / G and U % G: share b starts at unit b * q + (b * r) / G = floor(b * U / G)
+    uint64_t m_G, m_q, m_Us, m_pair_row, m_single_row, m_kt;  // reciprocals of G, q, Us, kWPair*V8, kWSingle*V8, kt
     // Arrival trees: which contexts have a draft row is known on the device only.  wprefix[c] = summed weights of
     // the contexts before c (kt + 1 entries, device memory); nullptr for the closed-form layouts above.
     const uint32_t* wprefix;
 };
+
+// Division of a 32-bit number by a fixed 32-bit divisor d through its 64-bit reciprocal m = floor(2^64 / d) + 1:
+// floor(n / d) = floor(n * m / 2^64) for every n < 2^32 (the product overshoots n / d by less than 2^-32, which
+// cannot reach the next integer because the fraction of n / d is at most 1 - 1/d).  m == 0 stands for d == 1.
+inline uint64_t magic_of(uint64_t d) { return d <= 1 ? 0 : ~(uint64_t)0 / d + 1; }
+__host__ __device__ inline uint32_t magic_div(uint32_t n, uint64_t m) {
+    if (!m) return n;
+    const uint64_t lo = (uint64_t)n * (uint32_t)m, hi = (uint64_t)n * (uint32_t)(m >> 32);
+    return (uint32_t)((hi + (lo >> 32)) >> 32);
+}
 
 // context whose cost units contain weighted position wpos (in units of one group): largest c with wprefix[c] <= wpos
 __host__ __device__ inline uint32_t part_table_row(const Part& p, uint64_t wpos) {
@@ -118,8 +134,37 @@ __host__ __device__ inline uint32_t part_table_row(const Part& p, uint64_t wpos)
     return lo;
 }
 
-__host__ __device__ inline uint64_t part_unit_to_pos(const Part& p, uint64_t u) {
-    if (u >= p.U) return p.rows * p.V8;
+struct PartPos {
+    uint64_t row;   // global row = seq * kt + j
+    uint64_t seq;
+    uint32_t j;     // row within the sequence
+    uint32_t grp;   // group within the row
+};
+
+// group that contains cost unit u (u >= U: the end)
+__host__ __device__ inline PartPos part_unit_to_pos(const Part& p, uint64_t u) {
+    PartPos o;
+    if (u >= p.U) {
+        o.row = p.rows;
+        o.seq = p.fast ? magic_div((uint32_t)p.rows, p.m_kt) : p.rows / p.kt;
+        o.j = 0;
+        o.grp = 0;
+        return o;
+    }
+    if (p.fast) {  // closed-form layout, everything below 2^32
+        const uint32_t u32 = (uint32_t)u, seq = magic_div(u32, p.m_Us), rem = u32 - seq * (uint32_t)p.Us;
+        o.seq = seq;
+        if (rem < (uint32_t)p.pair_units) {
+            o.j = magic_div(rem, p.m_pair_row);
+            o.grp = (rem - o.j * (kWPair * p.V8)) / kWPair;
+        } else {
+            const uint32_t r2 = rem - (uint32_t)p.pair_units, jj = magic_div(r2, p.m_single_row);
+            o.j = p.kd + jj;
+            o.grp = (r2 - jj * (kWSingle * p.V8)) / kWSingle;
+        }
+        o.row = (uint64_t)seq * p.kt + o.j;
+        return o;
+    }
     const uint64_t seq = u / p.Us, rem = u % p.Us;
     uint64_t row, grp;
     if (p.wprefix) {
@@ -133,15 +178,23 @@ __host__ __device__ inline uint64_t part_unit_to_pos(const Part& p, uint64_t u) 
         row = p.kd + r2 / ((uint64_t)kWSingle * p.V8);
         grp = (r2 % ((uint64_t)kWSingle * p.V8)) / kWSingle;
     }
-    return (seq * p.kt + row) * p.V8 + grp;
+    o.seq = seq;
+    o.j = (uint32_t)row;
+    o.grp = (uint32_t)grp;
+    o.row = seq * p.kt + row;
+    return o;
 }
-// first group (global index) of workgroup b's share; b == G gives the end
-__host__ __device__ inline uint64_t part_start_pos(const Part& p, uint32_t b) {
-    return part_unit_to_pos(p, (uint64_t)b * p.U / p.G);
+// first cost unit of workgroup b's share, floor(b * U / G); b == G gives U
+__host__ __device__ inline uint64_t part_block_start_unit(const Part& p, uint32_t b) {
+    if (p.fast) return (uint64_t)(b * p.q + magic_div(b * p.r, p.m_G));  // b * r < G^2 <= 2^24; the sum is <= U
+    return (uint64_t)b * p.U / p.G;
 }
-__host__ __device__ inline uint64_t part_row_unit(const Part& p, uint64_t row, uint32_t* w) {
-    const uint64_t seq = row / p.kt;
-    const uint32_t j = (uint32_t)(row % p.kt);
+// first group of workgroup b's share; b == G gives the end
+__host__ __device__ inline PartPos part_start_pos(const Part& p, uint32_t b) {
+    return part_unit_to_pos(p, part_block_start_unit(p, b));
+}
+// first cost unit and weight of row (seq, j)
+__host__ __device__ inline uint64_t part_row_unit(const Part& p, uint64_t seq, uint32_t j, uint32_t* w) {
     if (p.wprefix) {
         *w = p.wprefix[j + 1] - p.wprefix[j];
         return seq * p.Us + (uint64_t)p.wprefix[j] * p.V8;
@@ -149,17 +202,42 @@ __host__ __device__ inline uint64_t part_row_unit(const Part& p, uint64_t row, u
     *w = j < p.kd ? kWPair : kWSingle;
     return seq * p.Us + (j < p.kd ? (uint64_t)j * kWPair * p.V8 : p.pair_units + (uint64_t)(j - p.kd) * kWSingle * p.V8);
 }
-// workgroup that holds the first group of `row` (largest b whose share starts at or before it)
-__host__ __device__ inline uint32_t part_first_block(const Part& p, uint64_t row) {
-    uint32_t w;
-    const uint64_t u0 = part_row_unit(p, row, &w);
-    return (uint32_t)(((u0 + w) * p.G - 1) / p.U);
+// workgroup whose share contains cost unit x < U: the largest b with floor(b * U / G) <= x
+__host__ __device__ inline uint32_t part_block_of_unit(const Part& p, uint64_t x) {
+    if (p.fast) {
+        // b * q <= floor(b * U / G) < b * q + G and q > G (the quota), so the answer is floor(x / q) or one less
+        const uint32_t b = magic_div((uint32_t)x, p.m_q);
+        if (b >= p.G) return p.G - 1;
+        return part_block_start_unit(p, b) <= x ? b : b - 1;
+    }
+    return (uint32_t)(((x + 1) * p.G - 1) / p.U);
 }
-// workgroup that holds the last group of `row`
-__host__ __device__ inline uint32_t part_last_block(const Part& p, uint64_t row) {
+// workgroup that holds the first group of row (seq, j): a share starts at the group that contains its first unit,
+// so a group belongs to the last share that starts at or before the group's last unit
+__host__ __device__ inline uint32_t part_first_block(const Part& p, uint64_t seq, uint32_t j) {
     uint32_t w;
-    const uint64_t u1 = part_row_unit(p, row, &w) + (uint64_t)w * p.V8;
-    return (uint32_t)((u1 * p.G - 1) / p.U);
+    const uint64_t u0 = part_row_unit(p, seq, j, &w);
+    return part_block_of_unit(p, u0 + w - 1);
+}
+// workgroup that holds the last group of row (seq, j)
+__host__ __device__ inline uint32_t part_last_block(const Part& p, uint64_t seq, uint32_t j) {
+    uint32_t w;
+    const uint64_t u1 = part_row_unit(p, seq, j, &w) + (uint64_t)w * p.V8;
+    return part_block_of_unit(p, u1 - 1);
+}
+// number of segment slots of a global row
+__host__ __device__ inline uint32_t part_row_slots(const Part& p, uint64_t row) {
+    uint64_t seq;
+    uint32_t j;
+    if (p.fast) {
+        const uint32_t s32 = magic_div((uint32_t)row, p.m_kt);
+        seq = s32;
+        j = (uint32_t)row - s32 * p.kt;
+    } else {
+        seq = row / p.kt;
+        j = (uint32_t)(row % p.kt);
+    }
+    return part_last_block(p, seq, j) - part_first_block(p, seq, j) + 1;
 }
 
 struct RaceArgs {
@@ -169,6 +247,7 @@ struct RaceArgs {
     Part part;
     int32_t V;
     int32_t m;          // drafts per prompt
+    uint64_t m_m;       // reciprocal of m (magic_of)
     uint32_t pos0;      // position index of a sequence's first row (counter word 1 = pos0 + j)
     uint32_t key0, key1;
     float c2;           // log2(e) / T
@@ -801,22 +880,20 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(E
 race_kernel(RaceArgs a) {
     __shared__ Lds lds;
     const Part& p = a.part;
-    uint64_t pos = part_start_pos(p, blockIdx.x);
-    const uint64_t pos_end = part_start_pos(p, blockIdx.x + 1);
+    const PartPos first = part_start_pos(p, blockIdx.x), last = part_start_pos(p, blockIdx.x + 1);
     const size_t es = DT == ERSD_F32 ? 4 : 2;
-    if (pos >= pos_end) return;
     // (row, sequence, position, prompt, draft) of the first segment; later segments start at the next row's
     // first group, so they follow by counting up
-    uint64_t row = pos / p.V8;
-    uint32_t g0 = (uint32_t)(pos - row * p.V8);
-    uint64_t seq = row / p.kt;
-    uint32_t j = (uint32_t)(row - seq * p.kt);
-    uint32_t prompt = (uint32_t)(seq / a.m), d = (uint32_t)(seq - (uint64_t)prompt * a.m);
-    while (pos < pos_end) {  // one row segment per trip (workgroup-uniform)
+    uint64_t row = first.row;
+    uint32_t g0 = first.grp;
+    uint64_t seq = first.seq;
+    uint32_t j = first.j;
+    uint32_t prompt = p.fast ? magic_div((uint32_t)seq, a.m_m) : (uint32_t)(seq / a.m);
+    uint32_t d = (uint32_t)(seq - (uint64_t)prompt * a.m);
+    while (row < last.row || (row == last.row && g0 < last.grp)) {  // one row segment per trip (workgroup-uniform)
         Seg c;
         c.row = row;
-        const uint64_t left = pos_end - pos;
-        const uint32_t g1 = left < (uint64_t)(p.V8 - g0) ? g0 + (uint32_t)left : p.V8;
+        const uint32_t g1 = row == last.row ? last.grp : p.V8;
         c.prow = a.target + (size_t)row * (size_t)a.V * es;
         c.qrow = j < p.kd ? a.draft + (size_t)(seq * p.kd + j) * (size_t)a.V * es : nullptr;
         c.c1 = a.pos0 + j;
@@ -827,9 +904,8 @@ race_kernel(RaceArgs a) {
         const int64_t e = (int64_t)g1 * 8;
         c.end = e < a.V ? (int32_t)e : a.V;
         // a segment that starts at its row's first group is that row's first writer
-        c.slot = g0 == 0 ? 0 : blockIdx.x - part_first_block(p, row);
+        c.slot = g0 == 0 ? 0 : blockIdx.x - part_first_block(p, seq, j);
         race_segment<DT, VEC>(a, c, lds);
-        pos += g1 - g0;
         g0 = 0;
         ++row;
         if (++j == p.kt) {
@@ -982,19 +1058,16 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(E
 race_arrivals_kernel(RaceArgs a) {
     __shared__ Lds lds;
     const Part p = part_on_device(a.part);
-    uint64_t pos = part_start_pos(p, blockIdx.x);
-    const uint64_t pos_end = part_start_pos(p, blockIdx.x + 1);
+    const PartPos first = part_start_pos(p, blockIdx.x), last = part_start_pos(p, blockIdx.x + 1);
     const size_t es = DT == ERSD_F32 ? 4 : 2;
-    if (pos >= pos_end) return;
-    uint64_t row = pos / p.V8;
-    uint32_t g0 = (uint32_t)(pos - row * p.V8);
-    uint64_t seq = row / p.kt;
-    uint32_t j = (uint32_t)(row - seq * p.kt);  // context
-    while (pos < pos_end) {  // one row segment per trip (workgroup-uniform)
+    uint64_t row = first.row;
+    uint32_t g0 = first.grp;
+    uint64_t seq = first.seq;
+    uint32_t j = first.j;  // context
+    while (row < last.row || (row == last.row && g0 < last.grp)) {  // one row segment per trip (workgroup-uniform)
         Seg c;
         c.row = row;
-        const uint64_t left = pos_end - pos;
-        const uint32_t g1 = left < (uint64_t)(p.V8 - g0) ? g0 + (uint32_t)left : p.V8;
+        const uint32_t g1 = row == last.row ? last.grp : p.V8;
         c.nq = a.need[j];
         c.prow = a.target + (size_t)row * (size_t)a.V * es;
         c.qrow = c.nq > 0 ? a.draft + (size_t)row * (size_t)a.V * es : nullptr;
@@ -1004,9 +1077,8 @@ race_arrivals_kernel(RaceArgs a) {
         c.begin = (int32_t)(g0 * 8);
         const int64_t e = (int64_t)g1 * 8;
         c.end = e < a.V ? (int32_t)e : a.V;
-        c.slot = g0 == 0 ? 0 : blockIdx.x - part_first_block(p, row);
+        c.slot = g0 == 0 ? 0 : blockIdx.x - part_first_block(p, seq, j);
         race_segment_arr<DT, VEC>(a, c, lds);
-        pos += g1 - g0;
         g0 = 0;
         ++row;
         if (++j == p.kt) { j = 0; ++seq; }
@@ -1130,7 +1202,7 @@ __global__ void __launch_bounds__(kThreads) resolve_arrivals_kernel(ArrFinishArg
         const uint64_t trow = (uint64_t)blockIdx.x * (kThreads / 8) + (threadIdx.x >> 3);
         const bool active = trow < p.rows;
         const uint64_t r = active ? trow : 0;
-        const uint32_t n = active ? part_last_block(p, r) - part_first_block(p, r) + 1 : 0;
+        const uint32_t n = active ? part_row_slots(p, r) : 0;
         const int32_t tok = resolve_row(f.out + (r * 2 + 1) * p.nslot, n, f.T, active, threadIdx.x & 7);
         if (active && (threadIdx.x & 7) == 0) f.target_tokens[r] = tok;
         return;
@@ -1143,7 +1215,7 @@ __global__ void __launch_bounds__(kThreads) resolve_arrivals_kernel(ArrFinishArg
         if (lane < kMaxRank) arr[lane] = -1;
         return;
     }
-    const uint32_t nsl = part_last_block(p, row) - part_first_block(p, row) + 1;
+    const uint32_t nsl = part_row_slots(p, row);
     const SegOutArr* o = f.outq + row * p.nslot;
     const uint32_t total = nsl * kMaxArrSurvivors;
     constexpr int kKeep = 4;  // scores kept in registers per lane; a row with more candidates recomputes the rest
@@ -1326,7 +1398,7 @@ __global__ void __launch_bounds__(kThreads) resolve_kernel(FinishArgs f) {
     const uint32_t j = (uint32_t)(row % p.kt);
     const bool active = row < p.rows && (side == 1 || j < p.kd);
     const uint64_t r = active ? row : 0;
-    const uint32_t n = active ? part_last_block(p, r) - part_first_block(p, r) + 1 : 0;
+    const uint32_t n = active ? part_row_slots(p, r) : 0;
     const int32_t tok = resolve_row(f.out + (r * 2 + side) * p.nslot, n, f.T, active, tid & 7);
     if (active && (tid & 7) == 0) {
         if (side == 1) f.target_tokens[r] = tok;
@@ -1423,7 +1495,7 @@ __global__ void __launch_bounds__(kThreads) finish_kernel(FinishArgs f) {
         const uint32_t j = (uint32_t)(row % p.kt);
         const bool active = item < nitems && (side == 1 || j < p.kd);
         const uint64_t r = active ? row : row0;
-        const uint32_t n = active ? part_last_block(p, r) - part_first_block(p, r) + 1 : 0;
+        const uint32_t n = active ? part_row_slots(p, r) : 0;
         const int32_t tok = resolve_row(f.out + (r * 2 + side) * p.nslot, n, f.T, active, tid & 7);
         if (active && (tid & 7) == 0) {
             if (side == 1) f.target_tokens[r] = tok;
@@ -1513,6 +1585,19 @@ Part make_part(const Geometry& g, uint32_t blocks) {
     if (G < 1) G = 1;
     p.G = (uint32_t)G;
     p.nslot = (uint32_t)((uint64_t)kWPair * p.V8 * p.G / p.U) + 2;
+    p.fast = p.U < ((uint64_t)1 << 32) && p.rows < ((uint64_t)1 << 32) && p.U / p.G > p.G ? 1 : 0;
+    p.q = p.r = 0;
+    p.m_G = p.m_q = p.m_Us = p.m_pair_row = p.m_single_row = p.m_kt = 0;
+    if (p.fast) {
+        p.q = (uint32_t)(p.U / p.G);
+        p.r = (uint32_t)(p.U % p.G);
+        p.m_G = magic_of(p.G);
+        p.m_q = magic_of(p.q);
+        p.m_Us = magic_of(p.Us);
+        p.m_pair_row = magic_of((uint64_t)kWPair * p.V8);
+        p.m_single_row = magic_of((uint64_t)kWSingle * p.V8);
+        p.m_kt = magic_of(p.kt);
+    }
     return p;
 }
 
@@ -1575,6 +1660,7 @@ int launch_races(const void* dl, const void* tl, ersd_dtype dt, const Geometry& 
     a.out = static_cast<SegOut*>(ws);
     a.V = g.V;
     a.m = g.m;
+    a.m_m = magic_of((uint64_t)g.m);
     a.pos0 = pos0;
     a.key0 = (uint32_t)(seed & 0xffffffffu);
     a.key1 = (uint32_t)(seed >> 32);
@@ -1710,6 +1796,9 @@ int launch_arrival_tree(const void* dl, const void* tl, ersd_dtype dt, int32_t B
     p.pair_units = 0;
     p.Us = 0;                    // filled in on the device from the table
     p.U = 0;
+    p.fast = 0;                  // plain division: the totals are not known here
+    p.q = p.r = 0;
+    p.m_G = p.m_q = p.m_Us = p.m_pair_row = p.m_single_row = p.m_kt = 0;
     p.G = arrival_blocks(B, C, V, (uint32_t)blocks);
     p.nslot = arrival_nslot(B, C, p.G);
     p.wprefix = meta.wprefix;
@@ -1726,6 +1815,7 @@ int launch_arrival_tree(const void* dl, const void* tl, ersd_dtype dt, int32_t B
     a.part = p;
     a.V = V;
     a.m = 1;
+    a.m_m = 0;
     a.pos0 = 0;
     a.key0 = (uint32_t)(seed & 0xffffffffu);
     a.key1 = (uint32_t)(seed >> 32);
@@ -1952,11 +2042,14 @@ int ersd_plan_describe_host(int variant, int32_t B, int32_t m, int32_t k_or_N, i
     *out_G = p.G;
     *out_nslot = p.nslot;
     if (block_start)
-        for (uint32_t b = 0; b <= p.G; ++b) block_start[b] = part_start_pos(p, b);
+        for (uint32_t b = 0; b <= p.G; ++b) {
+            const PartPos s = part_start_pos(p, b);
+            block_start[b] = s.row * p.V8 + s.grp;
+        }
     if (row_first && row_last)
         for (uint64_t r = 0; r < p.rows; ++r) {
-            row_first[r] = part_first_block(p, r);
-            row_last[r] = part_last_block(p, r);
+            row_first[r] = part_first_block(p, r / p.kt, (uint32_t)(r % p.kt));
+            row_last[r] = part_last_block(p, r / p.kt, (uint32_t)(r % p.kt));
         }
     return ERSD_OK;
 }
