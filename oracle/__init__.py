@@ -72,6 +72,12 @@ def lib():
         L.oracle_race_verify_arrival_tree.restype = ctypes.c_int
         L.oracle_arrival_tree_shape.argtypes = [vp, vp, i32, i32, vp, vp]
         L.oracle_arrival_tree_shape.restype = None
+        L.oracle_gsd_verify.argtypes = [vp, vp, ctypes.c_int, i32, i32, i64, vp, f32, u64, vp, vp, vp]
+        L.oracle_gsd_verify.restype = ctypes.c_int
+        L.oracle_logsumexp.argtypes = [vp, ctypes.c_int, i64, f32]
+        L.oracle_logsumexp.restype = ctypes.c_double
+        L.oracle_gsd_uniform.argtypes = [u64, u32, u32]
+        L.oracle_gsd_uniform.restype = ctypes.c_double
         L.oracle_num_threads.restype = ctypes.c_int
         L.oracle_set_num_threads.argtypes = [ctypes.c_int]
         _LIB = L
@@ -290,4 +296,39 @@ def race_verify_arrival_tree(draft, target, parent, rank, temperature, seed, max
     out = dict(arrivals=arr, draft_tokens=dtok, target_tokens=ttok, accept_len=acc, accept_node=node, emitted=emitted)
     if want_info:
         out.update(arrival_near_tie=near, target_info=ti)
+    return out
+
+
+GSD_INFO_DTYPE = np.dtype([("near_accept", "<i4"), ("rivals", "<i4"), ("lse_p", "<f8"), ("lse_q", "<f8"),
+                           ("score", "<f8")], align=True)
+
+
+def logsumexp(row, temperature):
+    a, d = _host(row)
+    return lib().oracle_logsumexp(_ptr(a), d, a.shape[0], float(temperature))
+
+
+def gsd_uniform(seed, j, b):
+    return lib().oracle_gsd_uniform(int(seed), int(j), int(b))
+
+
+def gsd_verify(draft, target, draft_tokens, temperature, seed, want_info=False):
+    """GSD sequence verification: draft [B,k,V], target [B,k+1,V], draft_tokens [B,k] -> dict(accept_len, next_token)."""
+    d, dt = _host(draft)
+    t, dt2 = _host(target)
+    assert dt == dt2
+    B, k, V = d.shape
+    assert t.shape == (B, k + 1, V)
+    tok = np.ascontiguousarray(np.asarray(draft_tokens, dtype=np.int32))
+    assert tok.shape == (B, k)
+    acc = np.zeros(B, dtype=np.int32)
+    nxt = np.zeros(B, dtype=np.int32)
+    info = np.zeros(B, dtype=GSD_INFO_DTYPE) if want_info else None
+    rc = lib().oracle_gsd_verify(_ptr(d), _ptr(t), dt, B, k, V, _ptr(tok), float(temperature), int(seed), _ptr(acc),
+                                 _ptr(nxt), _ptr(info) if want_info else None)
+    if rc != 0:
+        raise ValueError("oracle_gsd_verify: invalid arguments")
+    out = dict(accept_len=acc, next_token=nxt)
+    if want_info:
+        out["info"] = info
     return out

@@ -425,3 +425,114 @@ int oracle_race_verify_arrival_tree(const void* draft, const void* target, int d
     free(need);
     return 0;
 }
+
+/* ---- GSD (Section 2, Algorithm 1 applied position by position): the comparison method ---- */
+
+/* log sum_i exp(l_i / T) of one row, two plain passes (maximum, then sum). -inf for a row without support. */
+double oracle_logsumexp(const void* row, int dtype, int64_t V, float temperature) {
+    const double T = (double)temperature;
+    double m = -INFINITY;
+    for (int64_t i = 0; i < V; ++i) {
+        const double z = widen(row, dtype, i) / T;
+        if (z > m) m = z;
+    }
+    if (!(m > -INFINITY) || m == INFINITY) return m;
+    double sum = 0.0;
+    for (int64_t i = 0; i < V; ++i) sum += exp(widen(row, dtype, i) / T - m);
+    return m + log(sum);
+}
+
+/* the uniform of the acceptance test at (sequence b, position j): word 0 of the counter (0, j, b, 2) */
+double oracle_gsd_uniform(uint64_t seed, uint32_t j, uint32_t b) {
+    const uint32_t key[2] = {(uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32)};
+    const uint32_t ctr[4] = {0u, j, b, 2u};
+    uint32_t w[4];
+    oracle_philox4x32(g_rounds, ctr, key, w);
+    return ((double)w[0] + 0.5) * (1.0 / 4294967296.0);
+}
+
+int oracle_gsd_verify(const void* draft, const void* target, int dtype, int32_t B, int32_t k, int64_t V,
+                      const int32_t* draft_tokens, float temperature, uint64_t seed,
+                      int32_t* accept_len, int32_t* next_token, oracle_gsd_info* info) {
+    if (bad_common(draft, target, dtype, V, temperature)) return -1;
+    if (B < 1 || k < 1 || !draft_tokens || !accept_len || !next_token) return -1;
+    for (int64_t t = 0; t < (int64_t)B * k; ++t)
+        if (draft_tokens[t] < 0 || draft_tokens[t] >= V) return -1;
+    const size_t es = elem_size(dtype);
+    const double T = (double)temperature;
+    const uint32_t key[2] = {(uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32)};
+    if (g_threads > 0) {
+#ifdef _OPENMP
+        omp_set_num_threads(g_threads);
+#endif
+    }
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t b = 0; b < B; ++b) {
+        /* verification: drafted tokens are tested in order until the first rejection */
+        int32_t a = 0;
+        int near_accept = 0;
+        double lse_p = 0.0, lse_q = 0.0;
+        for (; a < k; ++a) {
+            const char* qrow = (const char*)draft + (size_t)(((int64_t)b * k + a) * V) * es;
+            const char* prow = (const char*)target + (size_t)(((int64_t)b * (k + 1) + a) * V) * es;
+            lse_q = oracle_logsumexp(qrow, dtype, V, temperature);
+            lse_p = oracle_logsumexp(prow, dtype, V, temperature);
+            const int32_t x = draft_tokens[(int64_t)b * k + a];
+            /* P(x) / Q(x) > U */
+            const double ratio = exp((widen(prow, dtype, x) / T - lse_p) - (widen(qrow, dtype, x) / T - lse_q));
+            const double U = oracle_gsd_uniform(seed, (uint32_t)a, (uint32_t)b);
+            const double big = ratio > U ? ratio : U;
+            if (fabs(ratio - U) <= 1e-5 * big) near_accept = 1;
+            if (!(ratio > U)) break;
+        }
+        accept_len[b] = a;
+        /* next token: from the residual max(P - Q, 0) at the rejected position, or from P after the last draft;
+         * both drawn by an exponential race with the counter (i >> 2, a, b, 1) */
+        const char* prow = (const char*)target + (size_t)(((int64_t)b * (k + 1) + a) * V) * es;
+        const char* qrow = a < k ? (const char*)draft + (size_t)(((int64_t)b * k + a) * V) * es : NULL;
+        if (a == k) lse_p = oracle_logsumexp(prow, dtype, V, temperature);
+        int64_t best = -1;
+        double s1 = -INFINITY, floor1 = -INFINITY;
+        uint32_t words[4] = {0, 0, 0, 0};
+        for (int64_t i = 0; i < V; ++i) {
+            if ((i & 3) == 0) {
+                const uint32_t ctr[4] = {(uint32_t)(i >> 2), (uint32_t)a, (uint32_t)b, 1u};
+                oracle_philox4x32(g_rounds, ctr, key, words);
+            }
+            const double p = exp(widen(prow, dtype, i) / T - lse_p);
+            const double q = qrow ? exp(widen(qrow, dtype, i) / T - lse_q) : 0.0;
+            const double w = p - q > 0.0 ? p - q : 0.0;
+            const double score = log(w) + oracle_gumbel(words[i & 3]); /* argmin e_i / w_i */
+            if (best < 0 || score > s1) {
+                best = i;
+                s1 = score;
+                const double wl = w - 4e-6 * (p + q);
+                floor1 = wl > 0.0 ? log(wl) + oracle_gumbel(words[i & 3]) : -INFINITY;
+            }
+        }
+        next_token[b] = s1 > -INFINITY ? (int32_t)best : 0;
+        if (info) {
+            /* how many other tokens could win if every weight moved by 4e-6 (p + q): the sensitivity of the
+             * residual to errors of the two normalisers */
+            int32_t rivals = 0;
+            for (int64_t i = 0; i < V; ++i) {
+                if ((i & 3) == 0) {
+                    const uint32_t ctr[4] = {(uint32_t)(i >> 2), (uint32_t)a, (uint32_t)b, 1u};
+                    oracle_philox4x32(g_rounds, ctr, key, words);
+                }
+                if (i == best) continue;
+                const double p = exp(widen(prow, dtype, i) / T - lse_p);
+                const double q = qrow ? exp(widen(qrow, dtype, i) / T - lse_q) : 0.0;
+                const double w = p - q > 0.0 ? p - q : 0.0;
+                const double top = log(w + 4e-6 * (p + q)) + oracle_gumbel(words[i & 3]);
+                if (top >= floor1) ++rivals;
+            }
+            info[b].near_accept = near_accept;
+            info[b].rivals = rivals;
+            info[b].lse_p = lse_p;
+            info[b].lse_q = a < k ? lse_q : 0.0;
+            info[b].score = s1;
+        }
+    }
+    return 0;
+}

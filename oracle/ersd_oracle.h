@@ -148,6 +148,33 @@ int oracle_race_verify_arrival_tree(const void* draft, const void* target, int d
 void oracle_arrival_tree_shape(const int32_t* parent, const int32_t* rank, int32_t N, int32_t max_rank,
                                int32_t* valid, int32_t* need);
 
+/*
+ * GSD, the comparison method (Section 2; Algorithm 1 applied position by position, as the prose on the sequence
+ * strategy says: drafted tokens are verified in order until the first rejection).
+ *   draft [B,k,V], target [B,k+1,V], draft_tokens [B,k]: the tokens the drafting stage sampled from Q.
+ *   Position j of sequence b: P = softmax(l_p / T), Q = softmax(l_q / T); the drafted token x is accepted iff
+ *   P(x) / Q(x) > U with U = (w + 1/2) 2^-32, w = word 0 of the Philox counter (0, j, b, 2).
+ *   accept_len[b] = a = number of accepted tokens.  next_token[b]: if a < k a draw from the residual
+ *   max(P - Q, 0) / sum at position a, if a == k a draw from P at position k; both by an exponential race
+ *   argmin e_i / weight_i with e from the counter (i >> 2, a, b, 1) (the appendix notes that GSD's draws can be
+ *   made with races; any sampler would do).  A row whose weights are all zero gives token 0.
+ * info[b] (may be NULL): near_accept = 1 iff some tested ratio was within 1e-5 (relative) of its uniform;
+ * rivals = number of other tokens that could win the final race if every weight moved by 4e-6 (p + q), i.e. by
+ * what single-precision normalisers can shift it; lse_p, lse_q: normalisers at the last tested position.
+ */
+typedef struct {
+    int32_t near_accept;
+    int32_t rivals;
+    double lse_p, lse_q;
+    double score; /* winning score ln(weight) - ln(e) of the final race */
+} oracle_gsd_info;
+
+int oracle_gsd_verify(const void* draft, const void* target, int dtype, int32_t B, int32_t k, int64_t V,
+                      const int32_t* draft_tokens, float temperature, uint64_t seed,
+                      int32_t* accept_len, int32_t* next_token, oracle_gsd_info* info);
+double oracle_logsumexp(const void* row, int dtype, int64_t V, float temperature);
+double oracle_gsd_uniform(uint64_t seed, uint32_t j, uint32_t b);
+
 /* Threads the row loops will use (OpenMP), for reporting. */
 int oracle_num_threads(void);
 void oracle_set_num_threads(int n);
