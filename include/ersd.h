@@ -252,6 +252,29 @@ int ersd_tree_build_optimal_host(const double* accept_by_rank, int32_t nr, int32
  */
 int ersd_tree_build_specinfer_host(int32_t k, int32_t shared, int32_t branches, int32_t* parent, int32_t* rank);
 
+/*
+ * Verification by the comparison method, GSD (Section 2; Algorithm 1 applied position by position, as the text
+ * on the sequence strategy says), on the same kind of inputs as ersd_race_verify: it is here so that the cost of
+ * the two methods can be measured side by side.
+ *   draft_logits [B, k, V], target_logits [B, k + 1, V], draft_tokens [B, k] (DEVICE; the tokens the drafting
+ *   stage drew from Q = softmax(draft / T), each in [0, V) -- not checked; ersd_race_sample is one way to draw them).
+ *   Position j of sequence b accepts its drafted token x iff P(x) / Q(x) > U, U = (w + 1/2) 2^-32 with w = word 0
+ *   of the Philox counter (0, j, b, 2).  accept_len [B] out: tokens accepted before the first rejection, a.
+ *   next_token [B] out: for a < k a draw from the residual max(P - Q, 0) / sum at position a, for a == k a draw
+ *   from P at position k; both by an exponential race (argmin e_i / weight_i, e from the counter (i >> 2, a, b, 1),
+ *   lowest index on ties); a row whose weights are all zero gives token 0.
+ * The normalisers are accumulated in single precision, so an acceptance test whose ratio lies within about 1e-6
+ * (relative) of its uniform, or a residual whose two best scores are closer than what an error of 1e-6 (p + q) in
+ * the weights can move them, may resolve differently from an evaluation in double precision.
+ * Workspace size: ersd_gsd_workspace_bytes (0 for invalid sizes).  Same memory, stream and error rules as
+ * ersd_race_verify.
+ */
+int ersd_gsd_verify(const void* draft_logits, const void* target_logits, ersd_dtype dt,
+                    int32_t B, int32_t k, int32_t V, const int32_t* draft_tokens,
+                    float temperature, uint64_t seed, int32_t* accept_len, int32_t* next_token,
+                    void* workspace, size_t workspace_bytes, void* stream);
+size_t ersd_gsd_workspace_bytes(int32_t B, int32_t k, int32_t V, ersd_dtype dt);
+
 /* ERSD_MAX_RANK of the loaded library. */
 int ersd_max_rank(void);
 

@@ -6,6 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SRC = os.path.join(HERE, "csrc", "ersd_race.hip")
 SRC_HOST = os.path.join(HERE, "csrc", "ersd_tree.cpp")  # host-only part of the library
+SRC_GSD = os.path.join(HERE, "csrc", "ersd_gsd.hip")    # the comparison method
 LIB = os.path.join(HERE, "libersd.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
@@ -23,7 +24,7 @@ def build(extra=()):
     rounds = os.environ.get("ERSD_PHILOX_ROUNDS")  # 7 by default (set in the source); 10 = the generator's standard
     if rounds:
         extra = (*extra, f"-DERSD_PHILOX_ROUNDS={int(rounds)}")
-    cmd = [HIPCC, *FLAGS, *extra, "-o", LIB, SRC, SRC_HOST]
+    cmd = [HIPCC, *FLAGS, *extra, "-o", LIB, SRC, SRC_GSD, SRC_HOST]
     subprocess.run(cmd, check=True)
     return LIB
 

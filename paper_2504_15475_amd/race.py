@@ -63,6 +63,10 @@ def lib():
         L.ersd_arrival_tree_validate_host.argtypes = [vp, vp, i32]
         L.ersd_arrival_tree_validate_host.restype = ctypes.c_int
         L.ersd_max_rank.restype = ctypes.c_int
+        L.ersd_gsd_verify.argtypes = [vp, vp, ctypes.c_int, i32, i32, i32, vp, f32, u64, vp, vp, vp, sz, vp]
+        L.ersd_gsd_verify.restype = ctypes.c_int
+        L.ersd_gsd_workspace_bytes.argtypes = [i32, i32, i32, ctypes.c_int]
+        L.ersd_gsd_workspace_bytes.restype = sz
         L.ersd_tree_build_optimal_host.argtypes = [vp, i32, i32, vp, vp, vp, vp]
         L.ersd_tree_build_optimal_host.restype = ctypes.c_int
         L.ersd_tree_build_specinfer_host.argtypes = [i32, i32, i32, vp, vp]
@@ -419,3 +423,32 @@ def tree_build_specinfer(k, shared=2, branches=3):
     rank = np.empty(max(k, 0), dtype=np.int32)
     _check(lib().ersd_tree_build_specinfer_host(k, int(shared), int(branches), parent.ctypes.data, rank.ctypes.data))
     return parent, rank
+
+
+def gsd_workspace_bytes(B, k, V, dtype_code):
+    return int(lib().ersd_gsd_workspace_bytes(B, k, V, dtype_code))
+
+
+def gsd_verify(draft_logits, target_logits, draft_tokens, temperature, seed, workspace=None):
+    """The comparison method.  draft [B,k,V], target [B,k+1,V], draft_tokens int32 [B,k] -> (accept_len [B], next_token [B])."""
+    d, t = _dev(draft_logits, "draft_logits"), _dev(target_logits, "target_logits")
+    tok = _dev(draft_tokens, "draft_tokens")
+    code = _dtype_code(d)
+    if _dtype_code(t) != code:
+        raise TypeError("draft and target logits must share a dtype")
+    B, k, V = d.shape
+    if tuple(t.shape) != (B, k + 1, V):
+        raise ValueError(f"target_logits must be [B,k+1,V]=({B},{k + 1},{V}), got {tuple(t.shape)}")
+    if tok.dtype != torch.int32 or tuple(tok.shape) != (B, k):
+        raise ValueError("draft_tokens must be int32 [B,k]")
+    need = gsd_workspace_bytes(B, k, V, code)
+    if need == 0:
+        raise ErsdError(-2, status_string(-2))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=d.device)
+    acc = torch.empty((B,), dtype=torch.int32, device=d.device)
+    nxt = torch.empty((B,), dtype=torch.int32, device=d.device)
+    _check(lib().ersd_gsd_verify(d.data_ptr(), t.data_ptr(), code, B, k, V, tok.data_ptr(), float(temperature), int(seed),
+                                 acc.data_ptr(), nxt.data_ptr(), workspace.data_ptr(),
+                                 workspace.numel() * workspace.element_size(), _stream()))
+    return acc, nxt
