@@ -36,9 +36,10 @@ def main():
     ap.add_argument("--buffers", type=int, default=4, help="distinct input sets rotated through (cache defeat)")
     ap.add_argument("--event-every", type=int, default=8,
                     help="record HIP events around the race kernel of every N-th timed step (events cost a few us)")
-    ap.add_argument("--entry", choices=["verify", "sample"], default="verify",
+    ap.add_argument("--entry", choices=["verify", "sample", "gsd"], default="verify",
                     help="verify: the fused draft+target races (default, the headline metric); sample: the one-model "
-                         "entry point on the workload's target logits (how a serving loop calls the race)")
+                         "entry point on the workload's target logits (how a serving loop calls the race); gsd: the "
+                         "comparison method (ersd_gsd_verify) on the same logits, sequence workloads only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fused-call", action="store_true",
                     help="issue each step through the single verify entry point (no event between the stages)")
@@ -64,6 +65,8 @@ def main():
 
     if args.entry == "sample":
         return bench_sample(args, w, dev)
+    if args.entry == "gsd":
+        return bench_gsd(args, w, dev)
 
     base = wl.make_inputs(w, dev)
     sets = [base]
@@ -205,6 +208,58 @@ def bench_arrival_tree(args, w, dev):
                                 "kind": "oracle", "sample": f"first {nb} of {B} prompts, one pass",
                                 "check": {"mismatches_vs_oracle": mism}}
     print(json.dumps(line), flush=True)
+    return 0
+
+
+def bench_gsd(args, w, dev):
+    """The comparison method on a sequence workload's logits; events bracket the whole call (four kernels)."""
+    from paper_2504_15475_amd import race, workloads as wl
+    if w.variant != "sequence":
+        print("bench.py: --entry gsd needs a sequence workload (0, 1 or 2)", file=sys.stderr)
+        return 2
+    base = wl.make_inputs(w, dev)
+    sets = [base]
+    for _ in range(max(1, args.buffers) - 1):
+        sets.append(dict(draft=(base["draft"].float() + 0.01 * torch.randn(base["draft"].shape, device=dev))
+                         .to(w.dtype).contiguous(),
+                         target=(base["target"].float() + 0.01 * torch.randn(base["target"].shape, device=dev))
+                         .to(w.dtype).contiguous()))
+    for x in sets:  # the drafting stage is not part of verification
+        x["tokens"] = race.race_sample(x["draft"].unsqueeze(1), 0, w.temperature, w.seed)[:, 0].contiguous()
+    B, k, V = base["draft"].shape
+    ws = torch.empty(race.gsd_workspace_bytes(B, k, V, race._dtype_code(base["draft"])), dtype=torch.uint8, device=dev)
+
+    def step(i):
+        x = sets[i % len(sets)]
+        return race.gsd_verify(x["draft"], x["target"], x["tokens"], w.temperature, w.seed, workspace=ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    K = args.steps
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(K):
+        out = step(i)
+    e1.record()
+    torch.cuda.synchronize()
+    total_s = time.perf_counter() - t0
+    gpu_ms = e0.elapsed_time(e1) / K
+    # every drafted position's two rows once, then the two rows of the rejected position (or the last target row)
+    elements = B * (2 * k + 2) * V
+    nbytes = elements * w.elem_bytes
+    print(json.dumps({
+        "metric": "race_elements_per_sec", "value": elements * K / total_s, "unit": "elements/s", "n_gpus": 1,
+        "steps": K, "warmup": args.warmup, "ms_per_step": total_s * 1e3 / K, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "entry": "ersd_gsd_verify (comparison method)", "B": B, "k": k, "V": V,
+                   "mean_accept_len": float(out[0].float().mean())},
+        "roofline": {"bound": "hbm", "achieved": round(nbytes / (gpu_ms * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": round(nbytes / (gpu_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4), "traffic": None,
+                     "kernel": "whole call (normalisers, accept, residual, pick)", "kernel_ms_avg": round(gpu_ms, 5),
+                     "algorithmic_bytes_per_launch": nbytes},
+    }), flush=True)
     return 0
 
 

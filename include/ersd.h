@@ -257,7 +257,8 @@ int ersd_tree_build_specinfer_host(int32_t k, int32_t shared, int32_t branches, 
  * on the sequence strategy says), on the same kind of inputs as ersd_race_verify: it is here so that the cost of
  * the two methods can be measured side by side.
  *   draft_logits [B, k, V], target_logits [B, k + 1, V], draft_tokens [B, k] (DEVICE; the tokens the drafting
- *   stage drew from Q = softmax(draft / T), each in [0, V) -- not checked; ersd_race_sample is one way to draw them).
+ *   stage drew from Q = softmax(draft / T); ersd_race_sample is one way to draw them; a value outside [0, V) is
+ *   rejected at its position without being used as an index).
  *   Position j of sequence b accepts its drafted token x iff P(x) / Q(x) > U, U = (w + 1/2) 2^-32 with w = word 0
  *   of the Philox counter (0, j, b, 2).  accept_len [B] out: tokens accepted before the first rejection, a.
  *   next_token [B] out: for a < k a draw from the residual max(P - Q, 0) / sum at position a, for a == k a draw

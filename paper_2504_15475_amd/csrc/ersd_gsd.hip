@@ -179,49 +179,60 @@ struct AcceptArgs {
     uint32_t key0, key1;
 };
 
-// log2 of the sum over a row from its split partials, merged in double precision
+// log2 of the sum over a row from its split partials.  The rescaling 2^(m_s - m) and the final logarithm use the
+// single-precision hardware functions (a few 1e-7 of relative error, like the partial sums themselves); the sum
+// is kept in double precision.
 __device__ void row_normalisers(const float4* part, int32_t S, double& lse2_q, double& lse2_p) {
-    double mq = -INFINITY, mp = -INFINITY;
+    float mq = -INFINITY, mp = -INFINITY;
     for (int32_t s = 0; s < S; ++s) {
-        if (part[s].y > 0.0f) mq = fmax(mq, (double)part[s].x);
-        if (part[s].w > 0.0f) mp = fmax(mp, (double)part[s].z);
+        if (part[s].y > 0.0f) mq = fmaxf(mq, part[s].x);
+        if (part[s].w > 0.0f) mp = fmaxf(mp, part[s].z);
     }
     double sq = 0.0, sp = 0.0;
     for (int32_t s = 0; s < S; ++s) {
-        if (part[s].y > 0.0f) sq += (double)part[s].y * exp2((double)part[s].x - mq);
-        if (part[s].w > 0.0f) sp += (double)part[s].w * exp2((double)part[s].z - mp);
+        if (part[s].y > 0.0f) sq += (double)(part[s].y * __builtin_amdgcn_exp2f(part[s].x - mq));
+        if (part[s].w > 0.0f) sp += (double)(part[s].w * __builtin_amdgcn_exp2f(part[s].z - mp));
     }
-    lse2_q = sq > 0.0 ? mq + log2(sq) : -INFINITY;
-    lse2_p = sp > 0.0 ? mp + log2(sp) : -INFINITY;
+    lse2_q = sq > 0.0 ? (double)mq + (double)__builtin_amdgcn_logf((float)sq) : -INFINITY;
+    lse2_p = sp > 0.0 ? (double)mp + (double)__builtin_amdgcn_logf((float)sp) : -INFINITY;
 }
 
+// One workgroup per sequence: the positions are tested in parallel, then the first rejection is found.
 __global__ void __launch_bounds__(kThreads) gsd_accept_kernel(AcceptArgs a) {
-    const int32_t b = blockIdx.x * kThreads + threadIdx.x;
-    if (b >= a.g.B) return;
+    const int32_t b = blockIdx.x, tid = threadIdx.x;
     const int es = a.dt == ERSD_F32 ? 4 : 2;
-    int32_t acc = 0;
-    double lq = 0.0, lp = 0.0;
-    for (; acc < a.g.k; ++acc) {
-        const int64_t row = (int64_t)b * a.g.k + acc;
-        row_normalisers(a.partial + row * a.g.S1, a.g.S1, lq, lp);
+    __shared__ int32_t first_reject;
+    if (tid == 0) first_reject = a.g.k;
+    __syncthreads();
+    for (int32_t j = tid; j < a.g.k; j += kThreads) {
+        const int64_t row = (int64_t)b * a.g.k + j;
         const int32_t x = a.draft_tokens[row];
-        if (x < 0 || x >= a.g.V) break;  // not a token: rejected without touching the rows
-        const char* qrow = a.draft + (size_t)row * a.g.V * es;
-        const char* prow = a.target + (size_t)((int64_t)b * (a.g.k + 1) + acc) * a.g.V * es;
-        // P(x) / Q(x) > U
-        const double ratio = exp2(((double)widen(prow, a.dt, x) * a.c2 - lp) - ((double)widen(qrow, a.dt, x) * a.c2 - lq));
-        uint32_t w[4];
-        philox4x32(0u, (uint32_t)acc, (uint32_t)b, 2u, a.key0, a.key1, w);
-        const double U = ((double)w[0] + 0.5) * 0x1p-32;
-        if (!(ratio > U)) break;
+        bool ok = x >= 0 && x < a.g.V;  // not a token: rejected without touching the rows
+        if (ok) {
+            double lq, lp;
+            row_normalisers(a.partial + row * a.g.S1, a.g.S1, lq, lp);
+            const char* qrow = a.draft + (size_t)row * a.g.V * es;
+            const char* prow = a.target + (size_t)((int64_t)b * (a.g.k + 1) + j) * a.g.V * es;
+            // P(x) / Q(x) > U
+            const double ratio =
+                exp2(((double)widen(prow, a.dt, x) * a.c2 - lp) - ((double)widen(qrow, a.dt, x) * a.c2 - lq));
+            uint32_t w[4];
+            philox4x32(0u, (uint32_t)j, (uint32_t)b, 2u, a.key0, a.key1, w);
+            ok = ratio > ((double)w[0] + 0.5) * 0x1p-32;
+        }
+        if (!ok) atomicMin(&first_reject, j);
     }
-    a.accept_len[b] = acc;
-    Verdict v;
-    v.a = acc;
-    v.pad = 0;
-    v.lse2_p = lp;  // not used when every token was accepted: a draw from P needs no normaliser
-    v.lse2_q = lq;
-    a.verdict[b] = v;
+    __syncthreads();
+    if (tid == 0) {
+        const int32_t acc = first_reject;
+        a.accept_len[b] = acc;
+        Verdict v;
+        v.a = acc;
+        v.pad = 0;
+        v.lse2_p = v.lse2_q = 0.0;  // not used when every token was accepted: a draw from P needs no normaliser
+        if (acc < a.g.k) row_normalisers(a.partial + ((int64_t)b * a.g.k + acc) * a.g.S1, a.g.S1, v.lse2_q, v.lse2_p);
+        a.verdict[b] = v;
+    }
 }
 
 // log2 of e = -ln(1 - v), v = (x + 1/2) 2^-32, in single precision; |error| < 2^-7
@@ -275,6 +286,51 @@ __device__ double exact_score(const ResidualArgs& a, const char* qrow, const cha
 constexpr float kDelta = 1.0e-5f;
 constexpr float kLogErr = 0x1p-5f + 0x1p-10f;  // log2_exponential (2^-7), v_log_f32, and the final subtraction
 
+// four consecutive logits of a row (i a multiple of 4, in range): one 8- or 16-byte load when the row allows it
+template <bool VEC>
+__device__ __forceinline__ void load4(const char* row, int dt, int32_t i, int32_t end, float out[4]) {
+    if (VEC) {
+        if (dt == ERSD_F32) {
+            const u32x4 r = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + (size_t)i * 4));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) out[e] = __uint_as_float(r[e]);
+        } else {
+            typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+            const u32x2 r = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(row + (size_t)i * 2));
+            out[0] = __uint_as_float(r[0] << 16); out[1] = __uint_as_float(r[0] & 0xffff0000u);
+            out[2] = __uint_as_float(r[1] << 16); out[3] = __uint_as_float(r[1] & 0xffff0000u);
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) out[e] = i + e < end ? widen(row, dt, i + e) : -INFINITY;
+    }
+}
+
+// single-precision upper and lower score (log2 units) of one token; false if it cannot win
+__device__ __forceinline__ bool fast_scores(bool residual, float lp, float lq, float c2, float lp2, float lq2, uint32_t word,
+                                            float& up, float& down) {
+    down = -INFINITY;
+    if (residual) {
+        const float p = __builtin_amdgcn_exp2f(fmaf(lp, c2, -lp2));
+        const float q = __builtin_amdgcn_exp2f(fmaf(lq, c2, -lq2));
+        const float slack = kDelta * (p + q);
+        const float hi = p - q + slack, lo = p - q - slack;
+        if (!(hi > 0.0f)) return false;
+        const float l2e = log2_exponential(word);
+        up = __builtin_amdgcn_logf(hi) - l2e + kLogErr;
+        if (lo > 0.0f) down = __builtin_amdgcn_logf(lo) - l2e - kLogErr;
+    } else {  // a draw from P: the score is the scaled logit minus log2 e, no normaliser
+        const float z = lp * c2;
+        if (!(z > -INFINITY)) return false;
+        const float l2e = log2_exponential(word);
+        const float margin = kLogErr + fabsf(z) * 0x1p-20f;
+        up = z - l2e + margin;
+        down = z - l2e - margin;
+    }
+    return true;
+}
+
+template <bool VEC>
 __global__ void __launch_bounds__(kThreads) gsd_residual_kernel(ResidualArgs a) {
     const int tid = threadIdx.x;
     const int32_t b = blockIdx.x / a.g.S3, split = blockIdx.x % a.g.S3;
@@ -292,36 +348,48 @@ __global__ void __launch_bounds__(kThreads) gsd_residual_kernel(ResidualArgs a) 
     __shared__ uint32_t cword[kListCap];
     __shared__ double red_s[kWaves];
     __shared__ int32_t red_i[kWaves];
-    if (tid == 0) { tau = kNone; count = 0; }
-    __syncthreads();
+    __shared__ float red_t[kWaves];
+    if (tid == 0) count = 0;
+
+    // start from a lower bound of the best score: the best lower score among every lane's first group
+    float my_tau = kNone;
+    {
+        const int32_t g = (begin >> 2) + tid;
+        if (g * 4 < end) {
+            uint32_t w[4];
+            float lp[4], lq[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            philox4x32((uint32_t)g, (uint32_t)v.a, (uint32_t)b, 1u, a.key0, a.key1, w);
+            load4<VEC>(prow, a.dt, g * 4, end, lp);
+            if (residual) load4<VEC>(qrow, a.dt, g * 4, end, lq);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float up, down;
+                if (g * 4 + e < end && fast_scores(residual, lp[e], lq[e], a.c2, lp2, lq2, w[e], up, down))
+                    my_tau = fmaxf(my_tau, down);
+            }
+        }
+#pragma unroll
+        for (int off = kWave / 2; off > 0; off >>= 1) my_tau = fmaxf(my_tau, __shfl_xor(my_tau, off, kWave));
+        if ((tid & (kWave - 1)) == 0) red_t[tid / kWave] = my_tau;
+        __syncthreads();
+        for (int w = 0; w < kWaves; ++w) my_tau = fmaxf(my_tau, red_t[w]);
+        if (tid == 0) tau = my_tau;
+        __syncthreads();
+    }
 
     // every lane takes groups of four consecutive tokens (one generator call)
-    float my_tau = kNone;
     for (int32_t g = (begin >> 2) + tid; g * 4 < end; g += kThreads) {
         uint32_t w[4];
+        float lp[4], lq[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        load4<VEC>(prow, a.dt, g * 4, end, lp);
+        if (residual) load4<VEC>(qrow, a.dt, g * 4, end, lq);
         philox4x32((uint32_t)g, (uint32_t)v.a, (uint32_t)b, 1u, a.key0, a.key1, w);
         my_tau = fmaxf(my_tau, __hip_atomic_load(&tau, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int32_t i = g * 4 + e;
-            if (i >= end) break;
-            float up, down = -INFINITY;
-            const float l2e = log2_exponential(w[e]);
-            if (residual) {
-                const float p = __builtin_amdgcn_exp2f(fmaf(widen(prow, a.dt, i), a.c2, -lp2));
-                const float q = __builtin_amdgcn_exp2f(fmaf(widen(qrow, a.dt, i), a.c2, -lq2));
-                const float slack = kDelta * (p + q);
-                const float hi = p - q + slack, lo = p - q - slack;
-                if (!(hi > 0.0f)) continue;
-                up = __builtin_amdgcn_logf(hi) - l2e + kLogErr;
-                if (lo > 0.0f) down = __builtin_amdgcn_logf(lo) - l2e - kLogErr;
-            } else {  // a draw from P: the score is the scaled logit minus log2 e, no normaliser
-                const float z = widen(prow, a.dt, i) * a.c2;
-                if (!(z > -INFINITY)) continue;
-                const float margin = kLogErr + fabsf(z) * 0x1p-20f;
-                up = z - l2e + margin;
-                down = z - l2e - margin;
-            }
+            float up, down;
+            if (i >= end || !fast_scores(residual, lp[e], lq[e], a.c2, lp2, lq2, w[e], up, down)) continue;
             if (up >= my_tau) {
                 const int32_t pos = atomicAdd(&count, 1);
                 if (pos < kListCap) { cand[pos] = i; cword[pos] = w[e]; }
@@ -333,7 +401,7 @@ __global__ void __launch_bounds__(kThreads) gsd_residual_kernel(ResidualArgs a) 
         }
     }
     __syncthreads();
-    const double lse_p = residual ? v.lse2_p * 0.6931471805599453 : 0.0, lse_q = v.lse2_q * 0.6931471805599453;
+    const double lse_p = v.lse2_p * 0.6931471805599453, lse_q = v.lse2_q * 0.6931471805599453;
     double bs = -INFINITY;
     int32_t bi = -1;
     const int32_t n = count;
@@ -483,7 +551,7 @@ int ersd_gsd_verify(const void* draft_logits, const void* target_logits, ersd_dt
     aa.c2 = c2;
     aa.key0 = (uint32_t)(seed & 0xffffffffu);
     aa.key1 = (uint32_t)(seed >> 32);
-    hipLaunchKernelGGL(gsd_accept_kernel, dim3((uint32_t)((B + kThreads - 1) / kThreads)), block, 0, s, aa);
+    hipLaunchKernelGGL(gsd_accept_kernel, dim3((uint32_t)B), block, 0, s, aa);
 
     ResidualArgs ra;
     ra.draft = na.draft;
@@ -496,7 +564,8 @@ int ersd_gsd_verify(const void* draft_logits, const void* target_logits, ersd_dt
     ra.T = (double)temperature;
     ra.key0 = aa.key0;
     ra.key1 = aa.key1;
-    hipLaunchKernelGGL(gsd_residual_kernel, dim3((uint32_t)((int64_t)B * g.S3)), block, 0, s, ra);
+    if (vec) hipLaunchKernelGGL(gsd_residual_kernel<true>, dim3((uint32_t)((int64_t)B * g.S3)), block, 0, s, ra);
+    else hipLaunchKernelGGL(gsd_residual_kernel<false>, dim3((uint32_t)((int64_t)B * g.S3)), block, 0, s, ra);
     hipLaunchKernelGGL(gsd_pick_kernel, dim3((uint32_t)((B + kThreads - 1) / kThreads)), block, 0, s, ra.winner, B, g.S3,
                        next_token);
     return hipGetLastError() == hipSuccess ? ERSD_OK : ERSD_ERR_HIP;
