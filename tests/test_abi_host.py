@@ -163,3 +163,54 @@ def test_workload_generators_are_seeded_and_shaped():
     assert tuple(m["draft"].shape) == (2, 3, 2, 512) and tuple(m["target"].shape) == (2, 3, 3, 512)
     c2 = wl.make_inputs(wl.shrink(wl.WORKLOADS[2], B=2, k=2, V=4096))
     assert c2["target"].dtype == torch.float32 and float(c2["target"].max()) > 12.0     # boosted tokens present
+
+
+def test_arrival_tree_and_gsd_argument_errors(L):
+    def arr(**kw):
+        a = dict(d=FAKE, t=FAKE, dt=1, B=2, N=5, V=64, par=FAKE, rk=FAKE, T=1.0, seed=0, o=[FAKE] * 5, ws=FAKE,
+                 wsb=1 << 30)
+        a.update(kw)
+        return L.ersd_race_verify_arrival_tree(a["d"], a["t"], a["dt"], a["B"], a["N"], a["V"], a["par"], a["rk"],
+                                               a["T"], a["seed"], *a["o"], a["ws"], a["wsb"], None)
+    assert arr(d=None) == -1 and arr(t=None) == -1 and arr(par=None) == -1 and arr(rk=None) == -1 and arr(ws=None) == -1
+    for i in range(5):
+        o = [FAKE] * 5
+        o[i] = None
+        assert arr(o=o) == -1
+    assert arr(dt=7) == -3 and arr(T=0.0) == -2 and arr(T=float("nan")) == -2
+    assert arr(B=0) == -2 and arr(N=0) == -2 and arr(V=0) == -2 and arr(N=8193) == -2   # ERSD_MAX_ARRIVAL_TREE_NODES
+    assert arr(d=FAKE + 8) == -4 and arr(ws=FAKE + 4) == -4
+    assert arr(wsb=16) == -5
+    need = L.ersd_race_arrival_tree_workspace_bytes(2, 5, 64, 1)
+    assert need > 0 and arr(wsb=need - 1) == -5
+    assert L.ersd_race_arrival_tree_workspace_bytes(0, 5, 64, 1) == 0
+    assert L.ersd_race_arrival_tree_workspace_bytes(2, 5, 64, 9) == 0
+    assert L.ersd_max_rank() == 8
+
+    def gsd(**kw):
+        a = dict(d=FAKE, t=FAKE, dt=0, B=2, k=3, V=64, tok=FAKE, T=1.0, seed=0, o1=FAKE, o2=FAKE, ws=FAKE, wsb=1 << 30)
+        a.update(kw)
+        return L.ersd_gsd_verify(a["d"], a["t"], a["dt"], a["B"], a["k"], a["V"], a["tok"], a["T"], a["seed"], a["o1"],
+                                 a["o2"], a["ws"], a["wsb"], None)
+    assert gsd(d=None) == -1 and gsd(t=None) == -1 and gsd(tok=None) == -1 and gsd(o1=None) == -1 and gsd(o2=None) == -1
+    assert gsd(ws=None) == -1 and gsd(dt=3) == -3 and gsd(T=-2.0) == -2 and gsd(T=float("inf")) == -2
+    assert gsd(B=0) == -2 and gsd(k=0) == -2 and gsd(V=0) == -2 and gsd(B=2**30, k=2**10) == -2
+    assert gsd(t=FAKE + 2) == -4 and gsd(wsb=0) == -5
+    need = L.ersd_gsd_workspace_bytes(2, 3, 64, 0)
+    assert need > 0 and gsd(wsb=need - 1) == -5 and L.ersd_gsd_workspace_bytes(2, 0, 64, 0) == 0
+
+
+def test_tree_builders_argument_errors(L):
+    r = (ctypes.c_double * 2)(0.5, 0.2)
+    par = (ctypes.c_int32 * 4)()
+    rk = (ctypes.c_int32 * 4)()
+    assert L.ersd_tree_build_optimal_host(None, 2, 4, par, rk, None, None) == -1
+    assert L.ersd_tree_build_optimal_host(r, 2, 4, None, rk, None, None) == -1
+    assert L.ersd_tree_build_optimal_host(r, 0, 4, par, rk, None, None) == -2
+    assert L.ersd_tree_build_optimal_host(r, 2, 0, par, rk, None, None) == -2
+    assert L.ersd_tree_build_optimal_host(r, 2, 4, par, rk, None, None) == 0
+    assert list(par) == [-1, 0, -1, 1] and list(rk) == [0, 0, 1, 0]     # R: .5, .25, .2, .125
+    assert L.ersd_tree_build_specinfer_host(4, 2, 3, None, rk) == -1
+    assert L.ersd_tree_build_specinfer_host(0, 2, 3, par, rk) == -2
+    assert L.ersd_tree_build_specinfer_host(4, -1, 3, par, rk) == -2
+    assert L.ersd_tree_build_specinfer_host(4, 2, 0, par, rk) == -2
