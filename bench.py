@@ -22,7 +22,7 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per race-kernel launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a copy
 # kernel of known size; filled in from the summaries under profiles/ (None = not measured for that workload).
-MEASURED_TRAFFIC_BYTES = {1: 286144209, 2: 5171326896, 3: 1119049328, 4: 1068198315}
+MEASURED_TRAFFIC_BYTES = {1: 286314476, 2: 5171410747, 3: 1119068762, 4: 1068237715}
 
 
 def main():
