@@ -84,6 +84,36 @@ __device__ __forceinline__ MaxSum wave_merge(MaxSum v) {
     return v;
 }
 
+__device__ __forceinline__ float wave_max_f(float v) {
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+    return v;
+}
+
+// Eight logits of one lane into the wavefront's running (maximum, per-lane sum): the maximum is kept uniform over
+// the wavefront, so that it rises only a handful of times per row and the common case is one fused multiply-add,
+// one 2^x and one addition per logit.
+__device__ __forceinline__ void add_piece(float& m, float& s, const float (&l)[8], float c2) {
+    float t[8], top = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        t[e] = fmaf(l[e], c2, -m);
+        top = fmaxf(top, t[e]);
+    }
+    if (__builtin_amdgcn_ballot_w64(top > 0.0f) != 0) {  // rare: some lane saw a logit above the maximum
+        float zm = m;  // the new maximum from the scaled logits themselves (top + m would cancel against the start value)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) zm = fmaxf(zm, l[e] * c2);
+        const float m_new = wave_max_f(zm);
+        s *= __builtin_amdgcn_exp2f(m - m_new);
+        m = m_new;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) t[e] = fmaf(l[e], c2, -m);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s += __builtin_amdgcn_exp2f(t[e]);
+}
+
 struct Geometry {
     int32_t B, k, V;
     int32_t S1;      // vocabulary splits of the normaliser pass
@@ -116,7 +146,9 @@ __global__ void __launch_bounds__(kThreads) gsd_normaliser_kernel(NormArgs a) {
     if (VEC) {
         constexpr int kTok = 16 / es;  // tokens per 128-bit piece
         constexpr int kUnroll = 4;     // pieces in flight per row and lane
-        for (int32_t base = begin + tid * kTok; base < end; base += kThreads * kTok * kUnroll) {
+        // the trip count is the same for every lane: the lanes of a wavefront meet inside add_piece
+        for (int32_t tile = begin; tile < end; tile += kThreads * kTok * kUnroll) {
+            const int32_t base = tile + tid * kTok;
             u32x4 rq[kUnroll], rp[kUnroll];
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {  // unconditional loads from clamped addresses
@@ -126,22 +158,39 @@ __global__ void __launch_bounds__(kThreads) gsd_normaliser_kernel(NormArgs a) {
                 rp[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(prow + (size_t)c * es));
             }
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                if (base + u * kThreads * kTok < end) {
+            for (int u = 0; u < kUnroll; u += (DT == ERSD_F32 ? 2 : 1)) {
+                // a piece past the end re-read the last one: count it as masked (uniform control flow is kept
+                // because the wavefront's maximum is found together)
+                float lq[8], lp[8];
+                if (DT == ERSD_F32) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        if (DT == ERSD_F32) {
-                            add_value(q, __uint_as_float(rq[u][e]) * a.c2);
-                            add_value(p, __uint_as_float(rp[u][e]) * a.c2);
-                        } else {
-                            add_value(q, __uint_as_float(rq[u][e] << 16) * a.c2);
-                            add_value(q, __uint_as_float(rq[u][e] & 0xffff0000u) * a.c2);
-                            add_value(p, __uint_as_float(rp[u][e] << 16) * a.c2);
-                            add_value(p, __uint_as_float(rp[u][e] & 0xffff0000u) * a.c2);
+                    for (int h = 0; h < 2; ++h) {
+                        const bool in = base + (u + h) * kThreads * kTok < end;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            lq[h * 4 + e] = in ? __uint_as_float(rq[u + h][e]) : -INFINITY;
+                            lp[h * 4 + e] = in ? __uint_as_float(rp[u + h][e]) : -INFINITY;
                         }
                     }
+                } else {
+                    const bool in = base + u * kThreads * kTok < end;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        lq[2 * e] = in ? __uint_as_float(rq[u][e] << 16) : -INFINITY;
+                        lq[2 * e + 1] = in ? __uint_as_float(rq[u][e] & 0xffff0000u) : -INFINITY;
+                        lp[2 * e] = in ? __uint_as_float(rp[u][e] << 16) : -INFINITY;
+                        lp[2 * e + 1] = in ? __uint_as_float(rp[u][e] & 0xffff0000u) : -INFINITY;
+                    }
                 }
+                add_piece(q.m, q.s, lq, a.c2);
+                add_piece(p.m, p.s, lp, a.c2);
             }
+        }
+        // the maximum is uniform over the wavefront: add the lanes' sums
+#pragma unroll
+        for (int off = kWave / 2; off > 0; off >>= 1) {
+            q.s += __shfl_xor(q.s, off, kWave);
+            p.s += __shfl_xor(p.s, off, kWave);
         }
     } else {
         for (int32_t i = begin + tid; i < end; i += kThreads) {
@@ -149,8 +198,10 @@ __global__ void __launch_bounds__(kThreads) gsd_normaliser_kernel(NormArgs a) {
             add_value(p, widen(prow, DT, i) * a.c2);
         }
     }
-    q = wave_merge(q);
-    p = wave_merge(p);
+    if (!VEC) {
+        q = wave_merge(q);
+        p = wave_merge(p);
+    }
     __shared__ MaxSum sq[kWaves], sp[kWaves];
     if ((tid & (kWave - 1)) == 0) { sq[tid / kWave] = q; sp[tid / kWave] = p; }
     __syncthreads();
