@@ -264,3 +264,30 @@ def test_one_model_race_full_size_target_rows(race, oracle_mod):
     ref, info = oracle_mod.race_sample(x["target"].unsqueeze(1).contiguous().cpu(), 0, w.temperature, w.seed, want_info=True)
     assert info["near_tie"].sum() == 0
     assert np.array_equal(tok.cpu().numpy(), ref)
+
+
+def test_verify_call_can_be_captured_in_a_graph_and_replayed(race):
+    # the entry points allocate nothing, never synchronise and clear nothing with memsets: a captured call replays
+    # to the same outputs, also after other work on the device
+    w = wl.shrink(wl.WORKLOADS[1], B=8, k=4, V=65536)
+    x = wl.make_inputs(w, "cuda")
+    call = race.PreparedVerify(race.VARIANT_SEQUENCE, x["draft"], x["target"], w.temperature, w.seed)
+    call.run()
+    torch.cuda.synchronize()
+    ref = tuple(o.clone() for o in call.outputs())
+    s = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(g, stream=s):
+            call.run()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for o in call.outputs():
+            o.fill_(-7)
+        call.workspace.random_(0, 255)            # replays must not depend on what the workspace held
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert all(torch.equal(a, b) for a, b in zip(call.outputs(), ref)), f"replay {rep}"
+        y = torch.randn(1 << 20, device="cuda").sum().item()   # eager work between replays
+        assert y == y
