@@ -414,12 +414,15 @@ __device__ __forceinline__ Raw load_raw(const char* row, int32_t ia, int32_t ib,
         // Two unconditional 128-bit loads (no branch, so the compiler can count loads in flight exactly).  Piece
         // starts and `end` are multiples of the piece size and the segment is not empty; pieces past the end
         // re-read the segment's last piece instead, and the refine step never accepts a token index >= end.
+        // A row starts wherever the vocabulary size puts it, so the loads promise no more than element alignment
+        // (the hardware serves unaligned 128-bit global loads; aligned rows lose nothing).
+        typedef u32x4 u32x4_unaligned __attribute__((aligned(2)));
         constexpr int es = DT == ERSD_BF16 ? 2 : 4;
         const int32_t last = end - TileShape<DT, VEC>::kTokPerPiece;
         const int32_t ca = ia < last ? ia : last;
         const int32_t cb = ib < last ? ib : last;
-        r.a = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + (size_t)ca * es));
-        r.b = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + (size_t)cb * es));
+        r.a = __builtin_nontemporal_load(reinterpret_cast<const u32x4_unaligned*>(row + (size_t)ca * es));
+        r.b = __builtin_nontemporal_load(reinterpret_cast<const u32x4_unaligned*>(row + (size_t)cb * es));
     } else {  // element loads; registers hold fp32 bit patterns
         uint32_t f[8];
 #pragma unroll
@@ -685,8 +688,10 @@ __device__ __forceinline__ float wave_nth_largest(float v0, float v1, int32_t n)
     return m;
 }
 
+// The stream over a token range whose end is a multiple of 8 (or, with element loads, any end).  tauq / taup return
+// the lane's bounds.
 template <int DT, bool VEC, bool HASQ, bool ARR>
-__device__ void filter_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
+__device__ void filter_stream(const RaceArgs& a, const Seg& c, Lds& lds, float& tauq, float& taup) {
     constexpr bool RAWF32 = (DT == ERSD_F32) || !VEC;
     typedef TileShape<DT, VEC> TS;
     constexpr int kTile = TS::kTile;
@@ -709,7 +714,6 @@ __device__ void filter_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
 
     // Bootstrap: each wavefront starts from a lower bound of the maximum taken from the first two tokens of every
     // lane's first group (no barrier: the workgroup's bound in LDS is merged in at every tile).
-    float tauq = kTauInit, taup = kTauInit;
     {
         uint32_t w[4];
         philox4x32((uint32_t)first >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, w);
@@ -774,6 +778,37 @@ __device__ void filter_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
 #if ERSD_ROTATE_PRIO
     __builtin_amdgcn_s_setprio(0);
 #endif
+}
+
+// One segment: the 128-bit stream over its whole groups of 8 tokens, then the few tokens of a ragged row end (a
+// vocabulary size that is not a multiple of 8), which go straight to the refine step.
+template <int DT, bool VEC, bool HASQ, bool ARR>
+__device__ void filter_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
+    float tauq = kTauInit, taup = kTauInit;
+    if (!VEC) {
+        filter_stream<DT, VEC, HASQ, ARR>(a, c, lds, tauq, taup);
+        return;
+    }
+    const int32_t vend = c.end & ~7;  // c.begin is a multiple of 8
+    if (vend > c.begin) {
+        Seg v = c;
+        v.end = vend;
+        filter_stream<DT, VEC, HASQ, ARR>(a, v, lds, tauq, taup);
+    }
+    const int32_t i = vend + (int32_t)threadIdx.x;
+    if (i < c.end) {  // at most seven lanes
+        uint32_t w[4];
+        philox4x32((uint32_t)i >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, w);
+        const uint32_t x = pick4(u32x4{w[0], w[1], w[2], w[3]}, i & 3);
+        const float l2e = log2_exponential(x);
+        const float taup0 = taup, tauq0 = tauq;
+        refine_token(widen_elem(c.prow, DT, i), x, l2e, a.c2, i, taup, lds, 1, 0);
+        if (taup > taup0) lds_tau_raise(lds, 1, taup);
+        if (HASQ) {
+            refine_token(widen_elem(c.qrow, DT, i), x, l2e, a.c2, i, tauq, lds, 0, ARR ? c.nq : 0);
+            if (tauq > tauq0) lds_tau_raise(lds, 0, tauq);
+        }
+    }
 }
 
 // fp32 score of a (logit, word) record, exactly as the refine step computes it
@@ -1644,7 +1679,7 @@ int race_blocks(ersd_dtype dt, bool vec) {
 // the same way; `nslot` is capped by what the workspace was sized for.
 int plan_part(const Geometry& g, ersd_dtype dt, size_t ws_bytes, Part& p) {
     if (ws_bytes < workspace_for(g)) return ERSD_ERR_WORKSPACE_TOO_SMALL;
-    const int blocks = race_blocks(dt, (g.V % 8) == 0);
+    const int blocks = race_blocks(dt, true);
     if (blocks < 1) return ERSD_ERR_HIP;
     p = make_part(g, (uint32_t)blocks);
     return ERSD_OK;
@@ -1671,7 +1706,7 @@ int launch_races(const void* dl, const void* tl, ersd_dtype dt, const Geometry& 
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 grid(a.part.G), block(kThreads);
-    const bool vec = (g.V % 8) == 0;
+    const bool vec = true;  // rows of any vocabulary size take the 128-bit path
     if (dt == ERSD_F32) {
         if (vec) hipLaunchKernelGGL((race_kernel<ERSD_F32, true>), grid, block, 0, s, a);
         else hipLaunchKernelGGL((race_kernel<ERSD_F32, false>), grid, block, 0, s, a);
@@ -1778,7 +1813,7 @@ int launch_arrival_tree(const void* dl, const void* tl, ersd_dtype dt, int32_t B
                         const int32_t* parent, const int32_t* rank, float T, uint64_t seed, int32_t* dtok,
                         int32_t* ttok, int32_t* acc, int32_t* accept_node, int32_t* emitted, void* ws, void* stream) {
     const int32_t C = N + 1;
-    const bool vec = (V % 8) == 0;
+    const bool vec = true;
     const int blocks = arrival_race_blocks(dt, vec);
     if (blocks < 1) return ERSD_ERR_HIP;
     const ArrLayout l = arrival_layout(B, N, V);

@@ -69,7 +69,8 @@ def test_filter_bounds_hold_for_every_generator_word(race):
 
 
 SMALL = [
-    # several tiles plus a ragged tail, both dtypes, vocabulary multiples of 8 (128-bit loads) and not (element loads)
+    # several tiles plus a ragged tail, both dtypes, vocabulary sizes that are multiples of 8 and not (rows then start
+    # at every alignment and end in a group of fewer than 8 tokens)
     wl.shrink(wl.WORKLOADS[0], B=2, k=3, V=5000),
     wl.shrink(wl.WORKLOADS[0], B=2, k=2, V=4999),
     wl.shrink(wl.WORKLOADS[1], B=3, k=4, V=20008),
@@ -291,3 +292,17 @@ def test_verify_call_can_be_captured_in_a_graph_and_replayed(race):
         assert all(torch.equal(a, b) for a, b in zip(call.outputs(), ref)), f"replay {rep}"
         y = torch.randn(1 << 20, device="cuda").sum().item()   # eager work between replays
         assert y == y
+
+
+@pytest.mark.parametrize("tail", [1, 2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("idx", [1, 2], ids=["bf16", "f32"])
+def test_every_ragged_row_end_and_row_alignment(race, oracle_mod, idx, tail):
+    # V = 8 n + tail: rows begin at all element alignments and end in a group of `tail` tokens
+    run_case(race, oracle_mod, wl.shrink(wl.WORKLOADS[idx], B=3, k=3, V=16384 + tail), split=0)
+    run_case(race, oracle_mod, wl.shrink(wl.WORKLOADS[idx], B=2, k=2, V=8 + tail), split=5, note="barely more than a group")
+
+
+def test_vocabulary_smaller_than_a_group_and_gpt2_size(race, oracle_mod):
+    for V in (1, 2, 5, 7):
+        run_case(race, oracle_mod, wl.shrink(wl.WORKLOADS[0], B=4, k=2, V=V), note="no whole group")
+    run_case(race, oracle_mod, wl.shrink(wl.WORKLOADS[1], B=8, k=4, V=50257), note="odd vocabulary at full row length")
