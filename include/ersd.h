@@ -36,8 +36,8 @@
  *
  * Layout: tensors are row-major and contiguous with the vocabulary axis innermost; the draft and the
  * target tensor have the same element type.  Logit pointers must be 16-byte aligned, int32 outputs
- * 4-byte aligned, the workspace 16-byte aligned.  V may be any positive value; rows are streamed with
- * 128-bit loads when V is a multiple of 8 and with element loads otherwise.
+ * 4-byte aligned, the workspace 16-byte aligned.  V may be any positive value: rows are streamed with
+ * 128-bit loads whatever their alignment (a V that is not a multiple of 8 costs a few percent).
  *
  * Logit contents: -inf is a legal masked token and never wins unless its whole row is -inf, in which
  * case token 0 wins.  NaN logits give unspecified tokens (never a fault).

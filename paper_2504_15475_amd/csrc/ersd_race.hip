@@ -384,55 +384,43 @@ __device__ void exhaustive_half(const RaceArgs& a, const Seg& c, const char* row
 // ------------------------------------------------------------------------------------------ streaming filter
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-struct Raw {  // 8 logits as loaded: bf16 -> a only (4 dwords); fp32 (or element loads) -> a, b
+struct Raw {  // the two 16-byte pieces of a lane: bf16 -> 8 + 8 logits, fp32 -> 4 + 4
     u32x4 a, b;
 };
 
-constexpr uint32_t kNegInfF32 = 0xFF800000u;
 
 // Geometry of a tile.  With 128-bit loads every lane takes two 16-byte pieces per row and tile, and the pieces
 // are laid out so that each load instruction of a wavefront covers one contiguous kilobyte: lane t reads piece t
-// and piece kThreads + t of the tile.  The element-load path gives a lane 8 consecutive tokens instead.
-template <int DT, bool VEC>
+// and piece kThreads + t of the tile.
+template <int DT>
 struct TileShape {
-    static constexpr int kTokPerPiece = VEC ? (DT == ERSD_BF16 ? 8 : 4) : 4;
+    static constexpr int kTokPerPiece = DT == ERSD_BF16 ? 8 : 4;
     static constexpr int kTokPerThread = 2 * kTokPerPiece;
     static constexpr int kTile = kThreads * kTokPerThread;
     __device__ static __forceinline__ int32_t piece_a(int32_t tile_base, int tid) {
-        return tile_base + tid * (VEC ? kTokPerPiece : kTokPerThread);
+        return tile_base + tid * kTokPerPiece;
     }
     __device__ static __forceinline__ int32_t piece_b(int32_t tile_base, int tid) {
-        return VEC ? tile_base + (kThreads + tid) * kTokPerPiece : tile_base + tid * kTokPerThread + kTokPerPiece;
+        return tile_base + (kThreads + tid) * kTokPerPiece;
     }
 };
 
 // The two pieces of one lane: tokens [ia, ia + kTokPerPiece) and [ib, ib + kTokPerPiece).
-template <int DT, bool VEC>
+template <int DT>
 __device__ __forceinline__ Raw load_raw(const char* row, int32_t ia, int32_t ib, int32_t end) {
+    // Two unconditional 128-bit loads (no branch, so the compiler can count loads in flight exactly).  Piece starts
+    // and `end` are multiples of the piece size and the segment is not empty; pieces past the end re-read the
+    // segment's last piece instead, and the refine step never accepts a token index >= end.  A row starts wherever
+    // the vocabulary size puts it, so the loads promise no more than element alignment (the hardware serves
+    // unaligned 128-bit global loads; aligned rows lose nothing).
+    typedef u32x4 u32x4_unaligned __attribute__((aligned(2)));
+    constexpr int es = DT == ERSD_BF16 ? 2 : 4;
+    const int32_t last = end - TileShape<DT>::kTokPerPiece;
+    const int32_t ca = ia < last ? ia : last;
+    const int32_t cb = ib < last ? ib : last;
     Raw r;
-    if (VEC) {
-        // Two unconditional 128-bit loads (no branch, so the compiler can count loads in flight exactly).  Piece
-        // starts and `end` are multiples of the piece size and the segment is not empty; pieces past the end
-        // re-read the segment's last piece instead, and the refine step never accepts a token index >= end.
-        // A row starts wherever the vocabulary size puts it, so the loads promise no more than element alignment
-        // (the hardware serves unaligned 128-bit global loads; aligned rows lose nothing).
-        typedef u32x4 u32x4_unaligned __attribute__((aligned(2)));
-        constexpr int es = DT == ERSD_BF16 ? 2 : 4;
-        const int32_t last = end - TileShape<DT, VEC>::kTokPerPiece;
-        const int32_t ca = ia < last ? ia : last;
-        const int32_t cb = ib < last ? ib : last;
-        r.a = __builtin_nontemporal_load(reinterpret_cast<const u32x4_unaligned*>(row + (size_t)ca * es));
-        r.b = __builtin_nontemporal_load(reinterpret_cast<const u32x4_unaligned*>(row + (size_t)cb * es));
-    } else {  // element loads; registers hold fp32 bit patterns
-        uint32_t f[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int32_t i = e < 4 ? ia + e : ib + e - 4;
-            f[e] = i < end ? __float_as_uint(widen_elem(row, DT, i)) : kNegInfF32;
-        }
-        r.a = u32x4{f[0], f[1], f[2], f[3]};
-        r.b = u32x4{f[4], f[5], f[6], f[7]};
-    }
+    r.a = __builtin_nontemporal_load(reinterpret_cast<const u32x4_unaligned*>(row + (size_t)ca * es));
+    r.b = __builtin_nontemporal_load(reinterpret_cast<const u32x4_unaligned*>(row + (size_t)cb * es));
     return r;
 }
 
@@ -656,15 +644,15 @@ __device__ __forceinline__ void filter_tile(const RaceArgs& a, const Seg& c, Lds
 }
 
 // One lane's share of a tile: its two pieces.  A bf16 piece is 8 tokens and is filtered on its own; two fp32
-// pieces (or the 8 consecutive tokens of the element-load path) make one group of 8.
-template <int DT, bool VEC, bool HASQ, bool ARR>
+// pieces make one group of 8.
+template <int DT, bool HASQ, bool ARR>
 __device__ __forceinline__ void filter_lane(const RaceArgs& a, const Seg& c, Lds& lds, const HotConsts& h, int32_t ia,
                                             int32_t ib, const Raw& rq, const Raw& rp, float& tauq, float& taup) {
-    constexpr bool RAWF32 = (DT == ERSD_F32) || !VEC;
+    constexpr bool RAWF32 = DT == ERSD_F32;
     // the workgroup's bound, possibly raised by another wavefront since the last tile
     taup = fmaxf(taup, lds_tau(lds, 1));
     if (HASQ) tauq = fmaxf(tauq, lds_tau(lds, 0));
-    if (VEC && DT == ERSD_BF16) {
+    if (DT == ERSD_BF16) {
         Raw hq, hp;
         hq.a = rq.a; hq.b = rq.a; hp.a = rp.a; hp.b = rp.a;
         filter_tile<RAWF32, HASQ, ARR>(a, c, lds, h, ia, ia + 4, hq, hp, tauq, taup);
@@ -688,12 +676,11 @@ __device__ __forceinline__ float wave_nth_largest(float v0, float v1, int32_t n)
     return m;
 }
 
-// The stream over a token range whose end is a multiple of 8 (or, with element loads, any end).  tauq / taup return
-// the lane's bounds.
-template <int DT, bool VEC, bool HASQ, bool ARR>
+// The stream over a token range whose end is a multiple of 8.  tauq / taup return the lane's bounds.
+template <int DT, bool HASQ, bool ARR>
 __device__ void filter_stream(const RaceArgs& a, const Seg& c, Lds& lds, float& tauq, float& taup) {
-    constexpr bool RAWF32 = (DT == ERSD_F32) || !VEC;
-    typedef TileShape<DT, VEC> TS;
+    constexpr bool RAWF32 = DT == ERSD_F32;
+    typedef TileShape<DT> TS;
     constexpr int kTile = TS::kTile;
     const int tid = threadIdx.x;
     const float c2 = a.c2;
@@ -706,8 +693,8 @@ __device__ void filter_stream(const RaceArgs& a, const Seg& c, Lds& lds, float& 
 #pragma unroll
     for (int st = 0; st < kStages - 1; ++st) {
         const int32_t tb = c.begin + st * kTile;
-        pr[st] = load_raw<DT, VEC>(c.prow, TS::piece_a(tb, tid), TS::piece_b(tb, tid), c.end);
-        if (HASQ) q[st] = load_raw<DT, VEC>(c.qrow, TS::piece_a(tb, tid), TS::piece_b(tb, tid), c.end);
+        pr[st] = load_raw<DT>(c.prow, TS::piece_a(tb, tid), TS::piece_b(tb, tid), c.end);
+        if (HASQ) q[st] = load_raw<DT>(c.qrow, TS::piece_a(tb, tid), TS::piece_b(tb, tid), c.end);
     }
     const Raw& pa = pr[0];
     const Raw& qa = q[0];
@@ -767,9 +754,9 @@ __device__ void filter_stream(const RaceArgs& a, const Seg& c, Lds& lds, float& 
                 constexpr int kAhead = kStages - 1;
                 const int nb = (st + kAhead) % kStages;  // buffer of the tile kAhead tiles ahead
                 const int32_t nt = base + (st + kAhead) * kTile, ct = base + st * kTile;
-                pr[nb] = load_raw<DT, VEC>(c.prow, TS::piece_a(nt, tid), TS::piece_b(nt, tid), c.end);
-                if (HASQ) q[nb] = load_raw<DT, VEC>(c.qrow, TS::piece_a(nt, tid), TS::piece_b(nt, tid), c.end);
-                filter_lane<DT, VEC, HASQ, ARR>(a, c, lds, h, TS::piece_a(ct, tid), TS::piece_b(ct, tid), q[st], pr[st],
+                pr[nb] = load_raw<DT>(c.prow, TS::piece_a(nt, tid), TS::piece_b(nt, tid), c.end);
+                if (HASQ) q[nb] = load_raw<DT>(c.qrow, TS::piece_a(nt, tid), TS::piece_b(nt, tid), c.end);
+                filter_lane<DT, HASQ, ARR>(a, c, lds, h, TS::piece_a(ct, tid), TS::piece_b(ct, tid), q[st], pr[st],
                                            tauq, taup);
                 done = base + (st + 1) * kTile >= c.end;  // workgroup-uniform
             }
@@ -782,18 +769,14 @@ __device__ void filter_stream(const RaceArgs& a, const Seg& c, Lds& lds, float& 
 
 // One segment: the 128-bit stream over its whole groups of 8 tokens, then the few tokens of a ragged row end (a
 // vocabulary size that is not a multiple of 8), which go straight to the refine step.
-template <int DT, bool VEC, bool HASQ, bool ARR>
+template <int DT, bool HASQ, bool ARR>
 __device__ void filter_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
     float tauq = kTauInit, taup = kTauInit;
-    if (!VEC) {
-        filter_stream<DT, VEC, HASQ, ARR>(a, c, lds, tauq, taup);
-        return;
-    }
     const int32_t vend = c.end & ~7;  // c.begin is a multiple of 8
     if (vend > c.begin) {
         Seg v = c;
         v.end = vend;
-        filter_stream<DT, VEC, HASQ, ARR>(a, v, lds, tauq, taup);
+        filter_stream<DT, HASQ, ARR>(a, v, lds, tauq, taup);
     }
     const int32_t i = vend + (int32_t)threadIdx.x;
     if (i < c.end) {  // at most seven lanes
@@ -817,7 +800,7 @@ __device__ __forceinline__ float score2(float logit, uint32_t word, float c2) {
 }
 
 // A whole segment: stream, then hand the survivors of each side to the finishing kernel.
-template <int DT, bool VEC>
+template <int DT>
 __device__ void race_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
     const int tid = threadIdx.x;
     if (tid < 2) {
@@ -827,8 +810,8 @@ __device__ void race_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
     }
     __syncthreads();
     if (!a.exhaustive) {
-        if (c.qrow) filter_segment<DT, VEC, true, false>(a, c, lds);
-        else filter_segment<DT, VEC, false, false>(a, c, lds);
+        if (c.qrow) filter_segment<DT, true, false>(a, c, lds);
+        else filter_segment<DT, false, false>(a, c, lds);
     }
     __syncthreads();
 
@@ -910,7 +893,7 @@ __device__ void race_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
 #define ERSD_WAVES_PER_EU 3
 #endif
 
-template <int DT, bool VEC>
+template <int DT>
 __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ERSD_WAVES_PER_EU, 8)))
 race_kernel(RaceArgs a) {
     __shared__ Lds lds;
@@ -940,7 +923,7 @@ race_kernel(RaceArgs a) {
         c.end = e < a.V ? (int32_t)e : a.V;
         // a segment that starts at its row's first group is that row's first writer
         c.slot = g0 == 0 ? 0 : blockIdx.x - part_first_block(p, seq, j);
-        race_segment<DT, VEC>(a, c, lds);
+        race_segment<DT>(a, c, lds);
         g0 = 0;
         ++row;
         if (++j == p.kt) {
@@ -965,7 +948,7 @@ __device__ __forceinline__ Part part_on_device(const Part& in) {
     return p;
 }
 
-template <int DT, bool VEC>
+template <int DT>
 __device__ void race_segment_arr(const RaceArgs& a, const Seg& c, Lds& lds) {
     const int tid = threadIdx.x;
     if (tid < 2) {
@@ -977,8 +960,8 @@ __device__ void race_segment_arr(const RaceArgs& a, const Seg& c, Lds& lds) {
     if (tid == 0) lds.rounds = 0;
     __syncthreads();
     if (!a.exhaustive) {
-        if (c.qrow) filter_segment<DT, VEC, true, true>(a, c, lds);
-        else filter_segment<DT, VEC, false, true>(a, c, lds);
+        if (c.qrow) filter_segment<DT, true, true>(a, c, lds);
+        else filter_segment<DT, false, true>(a, c, lds);
     }
     __syncthreads();
 
@@ -1088,7 +1071,7 @@ __device__ void race_segment_arr(const RaceArgs& a, const Seg& c, Lds& lds) {
     if (my_rounds > 0 && half_tid == 0) *out_count = picked;
 }
 
-template <int DT, bool VEC>
+template <int DT>
 __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ERSD_WAVES_PER_EU, 8)))
 race_arrivals_kernel(RaceArgs a) {
     __shared__ Lds lds;
@@ -1113,7 +1096,7 @@ race_arrivals_kernel(RaceArgs a) {
         const int64_t e = (int64_t)g1 * 8;
         c.end = e < a.V ? (int32_t)e : a.V;
         c.slot = g0 == 0 ? 0 : blockIdx.x - part_first_block(p, seq, j);
-        race_segment_arr<DT, VEC>(a, c, lds);
+        race_segment_arr<DT>(a, c, lds);
         g0 = 0;
         ++row;
         if (++j == p.kt) { j = 0; ++seq; }
@@ -1665,21 +1648,19 @@ int resident_blocks(K kernel, std::atomic<int>& cache) {
 }
 
 // Workgroups the race kernel is launched with: as many as are resident at once on the current device.
-int race_blocks(ersd_dtype dt, bool vec) {
-    static std::atomic<int> cache[4];
+int race_blocks(ersd_dtype dt) {
+    static std::atomic<int> cache[2];
     const int forced = env_int("ERSD_FORCE_BLOCKS", 0);  // tests only
     if (forced > 0) return forced > (int)kMaxBlocks ? (int)kMaxBlocks : forced;
-    if (dt == ERSD_F32) return vec ? resident_blocks(race_kernel<ERSD_F32, true>, cache[0])
-                                   : resident_blocks(race_kernel<ERSD_F32, false>, cache[1]);
-    return vec ? resident_blocks(race_kernel<ERSD_BF16, true>, cache[2])
-               : resident_blocks(race_kernel<ERSD_BF16, false>, cache[3]);
+    return dt == ERSD_F32 ? resident_blocks(race_kernel<ERSD_F32>, cache[0])
+                          : resident_blocks(race_kernel<ERSD_BF16>, cache[1]);
 }
 
 // The partition both stages use.  It depends on the device (resident workgroups), so both stages recompute it
 // the same way; `nslot` is capped by what the workspace was sized for.
 int plan_part(const Geometry& g, ersd_dtype dt, size_t ws_bytes, Part& p) {
     if (ws_bytes < workspace_for(g)) return ERSD_ERR_WORKSPACE_TOO_SMALL;
-    const int blocks = race_blocks(dt, true);
+    const int blocks = race_blocks(dt);
     if (blocks < 1) return ERSD_ERR_HIP;
     p = make_part(g, (uint32_t)blocks);
     return ERSD_OK;
@@ -1706,14 +1687,8 @@ int launch_races(const void* dl, const void* tl, ersd_dtype dt, const Geometry& 
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 grid(a.part.G), block(kThreads);
-    const bool vec = true;  // rows of any vocabulary size take the 128-bit path
-    if (dt == ERSD_F32) {
-        if (vec) hipLaunchKernelGGL((race_kernel<ERSD_F32, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((race_kernel<ERSD_F32, false>), grid, block, 0, s, a);
-    } else {
-        if (vec) hipLaunchKernelGGL((race_kernel<ERSD_BF16, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((race_kernel<ERSD_BF16, false>), grid, block, 0, s, a);
-    }
+    if (dt == ERSD_F32) hipLaunchKernelGGL(race_kernel<ERSD_F32>, grid, block, 0, s, a);
+    else hipLaunchKernelGGL(race_kernel<ERSD_BF16>, grid, block, 0, s, a);
     return hipGetLastError() == hipSuccess ? ERSD_OK : ERSD_ERR_HIP;
 }
 
@@ -1799,22 +1774,19 @@ ArrLayout arrival_layout(int32_t B, int32_t N, int32_t V) {
     return l;
 }
 
-int arrival_race_blocks(ersd_dtype dt, bool vec) {
-    static std::atomic<int> cache[4];
+int arrival_race_blocks(ersd_dtype dt) {
+    static std::atomic<int> cache[2];
     const int forced = env_int("ERSD_FORCE_BLOCKS", 0);  // tests only
     if (forced > 0) return forced > (int)kMaxBlocks ? (int)kMaxBlocks : forced;
-    if (dt == ERSD_F32) return vec ? resident_blocks(race_arrivals_kernel<ERSD_F32, true>, cache[0])
-                                   : resident_blocks(race_arrivals_kernel<ERSD_F32, false>, cache[1]);
-    return vec ? resident_blocks(race_arrivals_kernel<ERSD_BF16, true>, cache[2])
-               : resident_blocks(race_arrivals_kernel<ERSD_BF16, false>, cache[3]);
+    return dt == ERSD_F32 ? resident_blocks(race_arrivals_kernel<ERSD_F32>, cache[0])
+                          : resident_blocks(race_arrivals_kernel<ERSD_BF16>, cache[1]);
 }
 
 int launch_arrival_tree(const void* dl, const void* tl, ersd_dtype dt, int32_t B, int32_t N, int32_t V,
                         const int32_t* parent, const int32_t* rank, float T, uint64_t seed, int32_t* dtok,
                         int32_t* ttok, int32_t* acc, int32_t* accept_node, int32_t* emitted, void* ws, void* stream) {
     const int32_t C = N + 1;
-    const bool vec = true;
-    const int blocks = arrival_race_blocks(dt, vec);
+    const int blocks = arrival_race_blocks(dt);
     if (blocks < 1) return ERSD_ERR_HIP;
     const ArrLayout l = arrival_layout(B, N, V);
     char* base = static_cast<char*>(ws);
@@ -1859,13 +1831,8 @@ int launch_arrival_tree(const void* dl, const void* tl, ersd_dtype dt, int32_t B
     const char* mode = std::getenv("ERSD_KERNEL");  // tests only
     a.exhaustive = mode && std::strcmp(mode, "exhaustive") == 0;
     const dim3 grid(p.G), block(kThreads);
-    if (dt == ERSD_F32) {
-        if (vec) hipLaunchKernelGGL((race_arrivals_kernel<ERSD_F32, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((race_arrivals_kernel<ERSD_F32, false>), grid, block, 0, s, a);
-    } else {
-        if (vec) hipLaunchKernelGGL((race_arrivals_kernel<ERSD_BF16, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((race_arrivals_kernel<ERSD_BF16, false>), grid, block, 0, s, a);
-    }
+    if (dt == ERSD_F32) hipLaunchKernelGGL(race_arrivals_kernel<ERSD_F32>, grid, block, 0, s, a);
+    else hipLaunchKernelGGL(race_arrivals_kernel<ERSD_BF16>, grid, block, 0, s, a);
 
     ArrFinishArgs af;
     af.out = a.out;
