@@ -40,7 +40,9 @@
  * 128-bit loads whatever their alignment (a V that is not a multiple of 8 costs a few percent).
  *
  * Logit contents: -inf is a legal masked token and never wins unless its whole row is -inf, in which
- * case token 0 wins.  NaN logits give unspecified tokens (never a fault).
+ * case token 0 wins.  Finite logits must satisfy |logit| / T < 2^100 (the streaming filter works in
+ * fp32; beyond that its products overflow).  NaN and +inf logits, and finite ones beyond that limit,
+ * give unspecified tokens (never a fault).
  *
  * Errors: every argument error is detected on the host before any HIP call is made and is returned
  * as a negative status; nothing is enqueued in that case.  ERSD_ERR_HIP reports a failed launch.

@@ -9,7 +9,8 @@
 //               -log2 e <= -log2 v = 32 - log2(x + 1/2) <= 159 - bits(float(x)) * 2^-23
 //             (e = -ln(1-v) >= v, and log2(1+f) >= f on [0,1] makes the float bit pattern a lower bound of
 //             log2).  A token is looked at again only if its bound reaches tau, a running LOWER bound
-//             of the row maximum.
+//             of the row maximum.  (The comparison is made in units of 2^-23 with 159 taken off both
+//             sides, so the bit pattern enters as it is; see tau_units.)
 //   refine  : for those few tokens an fp32 score with a proven error margin, using v_log_f32; tokens
 //             that can still be the maximum are appended to a candidate list in LDS and raise tau.
 //   survive : when a row segment has been streamed, only candidates whose fp32 interval still reaches the
@@ -427,12 +428,13 @@ __device__ __forceinline__ Raw load_raw(const char* row, int32_t ia, int32_t ib,
 // Operands the hot loop wants in vector registers: on gfx950 the simple VALU operations issue faster when none of
 // their sources is a scalar register or an inline constant, and the compiler would keep uniform values scalar.
 struct HotConsts {
-    float c2;        // log2(e) / T
+    float c2s;       // 2^23 * log2(e) / T: the logit's factor in the filter's fixed-point units (see bound_units)
     uint32_t sh16;   // the shift count 16
 };
 __device__ __forceinline__ HotConsts make_hot_consts(float c2) {
     HotConsts h;
-    asm volatile("v_mov_b32 %0, %1" : "=v"(h.c2) : "s"(c2));
+    const float c2s = c2 * 0x1p23f;
+    asm volatile("v_mov_b32 %0, %1" : "=v"(h.c2s) : "s"(c2s));
     asm volatile("v_mov_b32 %0, 16" : "=v"(h.sh16));
     return h;
 }
@@ -454,11 +456,18 @@ __device__ __forceinline__ void unpack(const Raw& r, float l[8], uint32_t sh16) 
     }
 }
 
-// Upper bound of -log2 e from the word x alone (see file header); slack is added to tau instead.
-__device__ __forceinline__ float gumbel2_upper(uint32_t x) {
+// The bit pattern of float(x), as a number: 2^23 * (127 + a piecewise-linear lower bound of log2 x).
+__device__ __forceinline__ float bound_units(uint32_t x) {
     const float xf = (float)x;
-    return fmaf((float)(int32_t)__float_as_uint(xf), -0x1p-23f, 159.0f);
+    return (float)(int32_t)__float_as_uint(xf);
 }
+// Upper bound of -log2 e from the word x alone (see file header); slack is added to tau instead.
+__device__ __forceinline__ float gumbel2_upper(uint32_t x) { return fmaf(bound_units(x), -0x1p-23f, 159.0f); }
+// The filter compares in units of 2^-23 with 159 taken off both sides, which saves the scaling of every token's
+// bound:  logit * c2 + gumbel2_upper(x) >= tau   <=>   logit * (2^23 c2) - bound_units(x) >= 2^23 (tau - 159).
+// Values stay below 2^32 in magnitude for scores of ordinary size, so one rounding costs 2^-24 * 2^9 log2 units,
+// far inside the margin with_margin() leaves; |logit| / T must stay below 2^100 for the product to be finite.
+__device__ __forceinline__ float tau_units(float tau_m) { return fmaf(tau_m, 0x1p23f, -159.0f * 0x1p23f); }
 
 // log2 of e = -ln(1 - v) in fp32.  |error| < 2^-7 given v_log_f32 within a few ulp (checked on device by
 // the library's self-test); callers use kRefineErr = 2^-5.
@@ -576,15 +585,15 @@ __device__ __forceinline__ float raw_logit_const(const Raw& r, int e) {
 template <bool RAWF32, bool HASQ>
 __device__ __forceinline__ void refine_tile(Lds& lds, float c2, int32_t i0, int32_t i1, int32_t end, const Raw& rq,
                                             const Raw& rp, const uint32_t (&x)[8], const float (&up)[8],
-                                            const float (&uq)[8], bool flag, float tauq_m, float taup_m, float& tauq,
+                                            const float (&uq)[8], bool flag, float tauq_u, float taup_u, float& tauq,
                                             float& taup, int32_t nq) {
     if (!flag) return;
     // which of this lane's (token, side) bounds reach tau: bits 0-7 target side, 8-15 draft side
     uint32_t mask = 0;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        if (up[e] >= taup_m) mask |= 1u << e;
-        if (HASQ && uq[e] >= tauq_m) mask |= 1u << (8 + e);
+        if (up[e] > taup_u) mask |= 1u << e;
+        if (HASQ && uq[e] > tauq_u) mask |= 1u << (8 + e);
     }
     const float taup0 = taup, tauq0 = tauq;
     while (mask) {  // usually a single bit in a single lane
@@ -612,9 +621,11 @@ __device__ __forceinline__ void refine_tile(Lds& lds, float c2, int32_t i0, int3
 template <bool RAWF32, bool HASQ, bool ARR>
 __device__ __forceinline__ void filter_tile(const RaceArgs& a, const Seg& c, Lds& lds, const HotConsts& h, int32_t i0,
                                             int32_t i1, const Raw& rq, const Raw& rp, float& tauq, float& taup) {
-    const float c2 = h.c2;
-    const float taup_m = with_margin(taup);
-    const float tauq_m = HASQ ? with_margin(tauq) : 0.0f;
+    // tau with its margin, in the filter's units.  The comparisons are strict, so a bound of -inf (a masked token)
+    // never passes, not even while tau is still at its start value (which these units turn into -inf).
+    const float c2s = h.c2s;
+    const float taup_u = tau_units(with_margin(taup));
+    const float tauq_u = HASQ ? tau_units(with_margin(tauq)) : 0.0f;
 
     uint32_t x[8];
     philox4x32((uint32_t)i0 >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, x);      // tokens i0 .. i0 + 3
@@ -624,22 +635,22 @@ __device__ __forceinline__ void filter_tile(const RaceArgs& a, const Seg& c, Lds
     if (HASQ) unpack<RAWF32>(rq, lq, h.sh16);
 
     float accp = -INFINITY, accq = -INFINITY;
-    float up[8], uq[8];  // per-token upper bounds of the two scores
+    float up[8], uq[8];  // per-token upper bounds of the two scores, in the filter's units
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        const float t = gumbel2_upper(x[e]);
-        up[e] = fmaf(lp[e], c2, t);
+        const float t = bound_units(x[e]);
+        up[e] = fmaf(lp[e], c2s, -t);
         accp = fmaxf(accp, up[e]);
         if (HASQ) {
-            uq[e] = fmaf(lq[e], c2, t);
+            uq[e] = fmaf(lq[e], c2s, -t);
             accq = fmaxf(accq, uq[e]);
         }
     }
-    bool flag = accp >= taup_m;
-    if (HASQ) flag = flag || (accq >= tauq_m);
+    bool flag = accp > taup_u;
+    if (HASQ) flag = flag || (accq > tauq_u);
 
     if (__builtin_amdgcn_ballot_w64(flag) != 0)  // rare: some lane holds a token that may matter
-        refine_tile<RAWF32, HASQ>(lds, a.c2, i0, i1, c.end, rq, rp, x, up, uq, flag, tauq_m, taup_m, tauq, taup,
+        refine_tile<RAWF32, HASQ>(lds, a.c2, i0, i1, c.end, rq, rp, x, up, uq, flag, tauq_u, taup_u, tauq, taup,
                                   ARR ? c.nq : 0);
 }
 
