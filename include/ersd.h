@@ -225,6 +225,40 @@ int ersd_race_verify_arrival_tree(const void* draft_logits, const void* target_l
                                   void* workspace, size_t workspace_bytes, void* stream);
 size_t ersd_race_arrival_tree_workspace_bytes(int32_t B, int32_t N, int32_t V, ersd_dtype dt);
 
+/*
+ * The same calls for logits whose rows do not lie back to back: a head that pads the vocabulary, or a slice
+ * [..., :V] of a wider tensor.  Row r of a tensor (r counts its leading axes in row-major order: (b, j),
+ * (b, d, j), (b, n) or (b, c)) starts `row_stride` ELEMENTS after row r - 1; each row is V contiguous
+ * elements.  row_stride >= V (else ERSD_ERR_INVALID_ARG); the two tensors may have different strides.  The
+ * base pointers must be 16-byte aligned as before, the rows themselves need element alignment only.
+ * Results, workspace sizes, stream and error rules are those of the call without `_strided`, which is the
+ * case row_stride == V.
+ */
+int ersd_race_verify_strided(const void* draft_logits, int64_t draft_row_stride, const void* target_logits,
+                             int64_t target_row_stride, ersd_dtype dt, int32_t B, int32_t k, int32_t V,
+                             float temperature, uint64_t seed, int32_t* draft_tokens, int32_t* target_tokens,
+                             int32_t* accept_len, void* workspace, size_t workspace_bytes, void* stream);
+int ersd_race_verify_multi_strided(const void* draft_logits, int64_t draft_row_stride, const void* target_logits,
+                                   int64_t target_row_stride, ersd_dtype dt, int32_t B, int32_t m, int32_t k,
+                                   int32_t V, float temperature, uint64_t seed, int32_t* draft_tokens,
+                                   int32_t* target_tokens, int32_t* accept_len, int32_t* best_draft,
+                                   int32_t* best_len, void* workspace, size_t workspace_bytes, void* stream);
+int ersd_race_verify_tree_strided(const void* draft_logits, int64_t draft_row_stride, const void* target_logits,
+                                  int64_t target_row_stride, ersd_dtype dt, int32_t B, int32_t N, int32_t V,
+                                  const int32_t* parent, float temperature, uint64_t seed, int32_t* draft_tokens,
+                                  int32_t* target_tokens, int32_t* accept_len, int32_t* accept_node,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+int ersd_race_sample_strided(const void* logits, int64_t row_stride, ersd_dtype dt, int32_t B, int32_t m,
+                             int32_t npos, int32_t V, int32_t pos0, float temperature, uint64_t seed,
+                             int32_t* tokens, void* workspace, size_t workspace_bytes, void* stream);
+int ersd_race_verify_arrival_tree_strided(const void* draft_logits, int64_t draft_row_stride,
+                                          const void* target_logits, int64_t target_row_stride, ersd_dtype dt,
+                                          int32_t B, int32_t N, int32_t V, const int32_t* parent,
+                                          const int32_t* rank, float temperature, uint64_t seed,
+                                          int32_t* draft_tokens, int32_t* target_tokens, int32_t* accept_len,
+                                          int32_t* accept_node, int32_t* emitted, void* workspace,
+                                          size_t workspace_bytes, void* stream);
+
 /* Host helper: 1 if every node of (parent, rank)[0..N) (HOST arrays) is valid by the rule above, else 0. */
 int ersd_arrival_tree_validate_host(const int32_t* parent_host, const int32_t* rank_host, int32_t N);
 

@@ -247,6 +247,7 @@ struct RaceArgs {
     SegOut* out;        // [row][side][slot]
     Part part;
     int32_t V;
+    int64_t qstride, pstride;  // elements between the starts of consecutive draft / target rows (>= V)
     int32_t m;          // drafts per prompt
     uint64_t m_m;       // reciprocal of m (magic_of)
     uint32_t pos0;      // position index of a sequence's first row (counter word 1 = pos0 + j)
@@ -923,8 +924,8 @@ race_kernel(RaceArgs a) {
         Seg c;
         c.row = row;
         const uint32_t g1 = row == last.row ? last.grp : p.V8;
-        c.prow = a.target + (size_t)row * (size_t)a.V * es;
-        c.qrow = j < p.kd ? a.draft + (size_t)(seq * p.kd + j) * (size_t)a.V * es : nullptr;
+        c.prow = a.target + (size_t)row * (size_t)a.pstride * es;
+        c.qrow = j < p.kd ? a.draft + (size_t)(seq * p.kd + j) * (size_t)a.qstride * es : nullptr;
         c.c1 = a.pos0 + j;
         c.c2 = prompt;
         c.c3 = d;
@@ -1098,8 +1099,8 @@ race_arrivals_kernel(RaceArgs a) {
         c.row = row;
         const uint32_t g1 = row == last.row ? last.grp : p.V8;
         c.nq = a.need[j];
-        c.prow = a.target + (size_t)row * (size_t)a.V * es;
-        c.qrow = c.nq > 0 ? a.draft + (size_t)row * (size_t)a.V * es : nullptr;
+        c.prow = a.target + (size_t)row * (size_t)a.pstride * es;
+        c.qrow = c.nq > 0 ? a.draft + (size_t)row * (size_t)a.qstride * es : nullptr;
         c.c1 = j;
         c.c2 = (uint32_t)seq;
         c.c3 = 0;
@@ -1566,7 +1567,13 @@ __global__ void zero_counters_kernel(unsigned long long* counters) {
 // ------------------------------------------------------------------------------------------ host side
 struct Geometry {
     int32_t B, m, kd, kt, V;
+    int64_t qstride, pstride;  // row strides in elements; 0 stands for V (rows back to back)
 };
+
+// a row stride is acceptable if rows do not overlap and the last row's end stays addressable
+bool stride_ok(int64_t stride, int32_t V, int64_t rows) {
+    return stride >= V && stride <= ((int64_t)1 << 40) && rows <= ((int64_t)1 << 60) / stride;
+}
 
 int env_int(const char* name, int dflt) {
     const char* s = std::getenv(name);
@@ -1590,6 +1597,7 @@ bool geometry(int variant, int32_t B, int32_t m, int32_t k_or_N, int32_t V, Geom
     if (k_or_N < 1 || k_or_N == 0x7fffffff) return false;
     g.B = B;
     g.V = V;
+    g.qstride = g.pstride = 0;
     if (variant == ERSD_VARIANT_SEQUENCE) { g.m = 1; g.kd = k_or_N; g.kt = k_or_N + 1; }
     else if (variant == ERSD_VARIANT_MULTI) { g.m = m; g.kd = k_or_N; g.kt = k_or_N + 1; }
     else if (variant == ERSD_VARIANT_TREE) { g.m = 1; g.kd = k_or_N; g.kt = k_or_N; }
@@ -1686,6 +1694,8 @@ int launch_races(const void* dl, const void* tl, ersd_dtype dt, const Geometry& 
     a.target = static_cast<const char*>(tl);
     a.out = static_cast<SegOut*>(ws);
     a.V = g.V;
+    a.qstride = g.qstride ? g.qstride : g.V;
+    a.pstride = g.pstride ? g.pstride : g.V;
     a.m = g.m;
     a.m_m = magic_of((uint64_t)g.m);
     a.pos0 = pos0;
@@ -1793,7 +1803,8 @@ int arrival_race_blocks(ersd_dtype dt) {
                           : resident_blocks(race_arrivals_kernel<ERSD_BF16>, cache[1]);
 }
 
-int launch_arrival_tree(const void* dl, const void* tl, ersd_dtype dt, int32_t B, int32_t N, int32_t V,
+int launch_arrival_tree(const void* dl, int64_t qstride, const void* tl, int64_t pstride, ersd_dtype dt, int32_t B,
+                        int32_t N, int32_t V,
                         const int32_t* parent, const int32_t* rank, float T, uint64_t seed, int32_t* dtok,
                         int32_t* ttok, int32_t* acc, int32_t* accept_node, int32_t* emitted, void* ws, void* stream) {
     const int32_t C = N + 1;
@@ -1832,6 +1843,8 @@ int launch_arrival_tree(const void* dl, const void* tl, ersd_dtype dt, int32_t B
     a.need = meta.need;
     a.part = p;
     a.V = V;
+    a.qstride = qstride;
+    a.pstride = pstride;
     a.m = 1;
     a.m_m = 0;
     a.pos0 = 0;
@@ -1877,19 +1890,33 @@ size_t ersd_race_arrival_tree_workspace_bytes(int32_t B, int32_t N, int32_t V, e
     return arrival_layout(B, N, V).total;
 }
 
-int ersd_race_verify_arrival_tree(const void* draft_logits, const void* target_logits, ersd_dtype dt, int32_t B,
-                                  int32_t N, int32_t V, const int32_t* parent, const int32_t* rank, float temperature,
-                                  uint64_t seed, int32_t* draft_tokens, int32_t* target_tokens, int32_t* accept_len,
-                                  int32_t* accept_node, int32_t* emitted, void* workspace, size_t workspace_bytes,
-                                  void* stream) {
+int ersd_race_verify_arrival_tree_strided(const void* draft_logits, int64_t draft_row_stride,
+                                          const void* target_logits, int64_t target_row_stride, ersd_dtype dt,
+                                          int32_t B, int32_t N, int32_t V, const int32_t* parent, const int32_t* rank,
+                                          float temperature, uint64_t seed, int32_t* draft_tokens,
+                                          int32_t* target_tokens, int32_t* accept_len, int32_t* accept_node,
+                                          int32_t* emitted, void* workspace, size_t workspace_bytes, void* stream) {
     if (!parent || !rank || !draft_tokens || !target_tokens || !accept_len || !accept_node || !emitted || !workspace)
         return ERSD_ERR_NULL_POINTER;
     const int rc = check_common(draft_logits, target_logits, dt, temperature, workspace);
     if (rc != ERSD_OK) return rc;
     if (!arrival_sizes_ok(B, N, V)) return ERSD_ERR_INVALID_ARG;
+    const int64_t rows = (int64_t)B * (N + 1);
+    if (!stride_ok(draft_row_stride, V, rows) || !stride_ok(target_row_stride, V, rows)) return ERSD_ERR_INVALID_ARG;
     if (workspace_bytes < arrival_layout(B, N, V).total) return ERSD_ERR_WORKSPACE_TOO_SMALL;
-    return launch_arrival_tree(draft_logits, target_logits, dt, B, N, V, parent, rank, temperature, seed, draft_tokens,
-                               target_tokens, accept_len, accept_node, emitted, workspace, stream);
+    return launch_arrival_tree(draft_logits, draft_row_stride, target_logits, target_row_stride, dt, B, N, V, parent,
+                               rank, temperature, seed, draft_tokens, target_tokens, accept_len, accept_node, emitted,
+                               workspace, stream);
+}
+
+int ersd_race_verify_arrival_tree(const void* draft_logits, const void* target_logits, ersd_dtype dt, int32_t B,
+                                  int32_t N, int32_t V, const int32_t* parent, const int32_t* rank, float temperature,
+                                  uint64_t seed, int32_t* draft_tokens, int32_t* target_tokens, int32_t* accept_len,
+                                  int32_t* accept_node, int32_t* emitted, void* workspace, size_t workspace_bytes,
+                                  void* stream) {
+    return ersd_race_verify_arrival_tree_strided(draft_logits, V, target_logits, V, dt, B, N, V, parent, rank,
+                                                 temperature, seed, draft_tokens, target_tokens, accept_len,
+                                                 accept_node, emitted, workspace, workspace_bytes, stream);
 }
 
 int ersd_arrival_tree_validate_host(const int32_t* parent_host, const int32_t* rank_host, int32_t N) {
@@ -1942,57 +1969,94 @@ int ersd_race_stage_accept(int variant, ersd_dtype dt, int32_t B, int32_t m, int
                          best_len, accept_node, workspace, workspace_bytes, stream);
 }
 
-int ersd_race_verify(const void* draft_logits, const void* target_logits, ersd_dtype dt, int32_t B, int32_t k,
-                     int32_t V, float temperature, uint64_t seed, int32_t* draft_tokens, int32_t* target_tokens,
-                     int32_t* accept_len, void* workspace, size_t workspace_bytes, void* stream) {
+// The three fused calls share one body: sizes and strides checked on the host, then race and finishing kernels.
+static int verify_any(int variant, const void* draft_logits, int64_t draft_row_stride, const void* target_logits,
+                      int64_t target_row_stride, ersd_dtype dt, int32_t B, int32_t m, int32_t k_or_N, int32_t V,
+                      const int32_t* parent, float temperature, uint64_t seed, int32_t* draft_tokens,
+                      int32_t* target_tokens, int32_t* accept_len, int32_t* best_draft, int32_t* best_len,
+                      int32_t* accept_node, void* workspace, size_t workspace_bytes, void* stream) {
     if (!draft_tokens || !target_tokens || !accept_len || !workspace) return ERSD_ERR_NULL_POINTER;
+    if (variant == ERSD_VARIANT_MULTI && (!best_draft || !best_len)) return ERSD_ERR_NULL_POINTER;
+    if (variant == ERSD_VARIANT_TREE && !parent) return ERSD_ERR_NULL_POINTER;
     const int rc = check_common(draft_logits, target_logits, dt, temperature, workspace);
     if (rc != ERSD_OK) return rc;
     Geometry g;
-    if (!geometry(ERSD_VARIANT_SEQUENCE, B, 1, k, V, g)) return ERSD_ERR_INVALID_ARG;
+    if (!geometry(variant, B, m, k_or_N, V, g)) return ERSD_ERR_INVALID_ARG;
+    if (!stride_ok(draft_row_stride, V, (int64_t)g.B * g.m * g.kd) ||
+        !stride_ok(target_row_stride, V, (int64_t)g.B * g.m * g.kt))
+        return ERSD_ERR_INVALID_ARG;
+    g.qstride = draft_row_stride;
+    g.pstride = target_row_stride;
     if (workspace_bytes < workspace_for(g)) return ERSD_ERR_WORKSPACE_TOO_SMALL;
-    return launch(draft_logits, target_logits, dt, g, temperature, seed, ERSD_VARIANT_SEQUENCE, nullptr, draft_tokens,
-                  target_tokens, accept_len, nullptr, nullptr, nullptr, workspace, workspace_bytes, stream);
+    return launch(draft_logits, target_logits, dt, g, temperature, seed, variant, parent, draft_tokens, target_tokens,
+                  accept_len, best_draft, best_len, accept_node, workspace, workspace_bytes, stream);
+}
+
+int ersd_race_verify_strided(const void* draft_logits, int64_t draft_row_stride, const void* target_logits,
+                             int64_t target_row_stride, ersd_dtype dt, int32_t B, int32_t k, int32_t V,
+                             float temperature, uint64_t seed, int32_t* draft_tokens, int32_t* target_tokens,
+                             int32_t* accept_len, void* workspace, size_t workspace_bytes, void* stream) {
+    return verify_any(ERSD_VARIANT_SEQUENCE, draft_logits, draft_row_stride, target_logits, target_row_stride, dt, B, 1,
+                      k, V, nullptr, temperature, seed, draft_tokens, target_tokens, accept_len, nullptr, nullptr,
+                      nullptr, workspace, workspace_bytes, stream);
+}
+
+int ersd_race_verify_multi_strided(const void* draft_logits, int64_t draft_row_stride, const void* target_logits,
+                                   int64_t target_row_stride, ersd_dtype dt, int32_t B, int32_t m, int32_t k,
+                                   int32_t V, float temperature, uint64_t seed, int32_t* draft_tokens,
+                                   int32_t* target_tokens, int32_t* accept_len, int32_t* best_draft,
+                                   int32_t* best_len, void* workspace, size_t workspace_bytes, void* stream) {
+    return verify_any(ERSD_VARIANT_MULTI, draft_logits, draft_row_stride, target_logits, target_row_stride, dt, B, m, k,
+                      V, nullptr, temperature, seed, draft_tokens, target_tokens, accept_len, best_draft, best_len,
+                      nullptr, workspace, workspace_bytes, stream);
+}
+
+int ersd_race_verify_tree_strided(const void* draft_logits, int64_t draft_row_stride, const void* target_logits,
+                                  int64_t target_row_stride, ersd_dtype dt, int32_t B, int32_t N, int32_t V,
+                                  const int32_t* parent, float temperature, uint64_t seed, int32_t* draft_tokens,
+                                  int32_t* target_tokens, int32_t* accept_len, int32_t* accept_node, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
+    return verify_any(ERSD_VARIANT_TREE, draft_logits, draft_row_stride, target_logits, target_row_stride, dt, B, 1, N,
+                      V, parent, temperature, seed, draft_tokens, target_tokens, accept_len, nullptr, nullptr,
+                      accept_node, workspace, workspace_bytes, stream);
+}
+
+int ersd_race_verify(const void* draft_logits, const void* target_logits, ersd_dtype dt, int32_t B, int32_t k,
+                     int32_t V, float temperature, uint64_t seed, int32_t* draft_tokens, int32_t* target_tokens,
+                     int32_t* accept_len, void* workspace, size_t workspace_bytes, void* stream) {
+    return ersd_race_verify_strided(draft_logits, V, target_logits, V, dt, B, k, V, temperature, seed, draft_tokens,
+                                    target_tokens, accept_len, workspace, workspace_bytes, stream);
 }
 
 int ersd_race_verify_multi(const void* draft_logits, const void* target_logits, ersd_dtype dt, int32_t B, int32_t m,
                            int32_t k, int32_t V, float temperature, uint64_t seed, int32_t* draft_tokens,
                            int32_t* target_tokens, int32_t* accept_len, int32_t* best_draft, int32_t* best_len,
                            void* workspace, size_t workspace_bytes, void* stream) {
-    if (!draft_tokens || !target_tokens || !accept_len || !best_draft || !best_len || !workspace)
-        return ERSD_ERR_NULL_POINTER;
-    const int rc = check_common(draft_logits, target_logits, dt, temperature, workspace);
-    if (rc != ERSD_OK) return rc;
-    Geometry g;
-    if (!geometry(ERSD_VARIANT_MULTI, B, m, k, V, g)) return ERSD_ERR_INVALID_ARG;
-    if (workspace_bytes < workspace_for(g)) return ERSD_ERR_WORKSPACE_TOO_SMALL;
-    return launch(draft_logits, target_logits, dt, g, temperature, seed, ERSD_VARIANT_MULTI, nullptr, draft_tokens,
-                  target_tokens, accept_len, best_draft, best_len, nullptr, workspace, workspace_bytes, stream);
+    return ersd_race_verify_multi_strided(draft_logits, V, target_logits, V, dt, B, m, k, V, temperature, seed,
+                                          draft_tokens, target_tokens, accept_len, best_draft, best_len, workspace,
+                                          workspace_bytes, stream);
 }
 
 int ersd_race_verify_tree(const void* draft_logits, const void* target_logits, ersd_dtype dt, int32_t B, int32_t N,
                           int32_t V, const int32_t* parent, float temperature, uint64_t seed, int32_t* draft_tokens,
                           int32_t* target_tokens, int32_t* accept_len, int32_t* accept_node, void* workspace,
                           size_t workspace_bytes, void* stream) {
-    if (!parent || !draft_tokens || !target_tokens || !accept_len || !workspace) return ERSD_ERR_NULL_POINTER;
-    const int rc = check_common(draft_logits, target_logits, dt, temperature, workspace);
-    if (rc != ERSD_OK) return rc;
-    Geometry g;
-    if (!geometry(ERSD_VARIANT_TREE, B, 1, N, V, g)) return ERSD_ERR_INVALID_ARG;
-    if (workspace_bytes < workspace_for(g)) return ERSD_ERR_WORKSPACE_TOO_SMALL;
-    return launch(draft_logits, target_logits, dt, g, temperature, seed, ERSD_VARIANT_TREE, parent, draft_tokens,
-                  target_tokens, accept_len, nullptr, nullptr, accept_node, workspace, workspace_bytes, stream);
+    return ersd_race_verify_tree_strided(draft_logits, V, target_logits, V, dt, B, N, V, parent, temperature, seed,
+                                         draft_tokens, target_tokens, accept_len, accept_node, workspace,
+                                         workspace_bytes, stream);
 }
 
-int ersd_race_sample(const void* logits, ersd_dtype dt, int32_t B, int32_t m, int32_t npos, int32_t V, int32_t pos0,
-                     float temperature, uint64_t seed, int32_t* tokens, void* workspace, size_t workspace_bytes,
-                     void* stream) {
+int ersd_race_sample_strided(const void* logits, int64_t row_stride, ersd_dtype dt, int32_t B, int32_t m,
+                             int32_t npos, int32_t V, int32_t pos0, float temperature, uint64_t seed, int32_t* tokens,
+                             void* workspace, size_t workspace_bytes, void* stream) {
     if (!tokens || !workspace) return ERSD_ERR_NULL_POINTER;
     const int rc = check_common(logits, logits, dt, temperature, workspace);
     if (rc != ERSD_OK) return rc;
     Geometry g;
     g.B = B; g.m = m; g.kd = 0; g.kt = npos; g.V = V;  // every row is raced on its own
-    if (npos < 1 || pos0 < 0 || (int64_t)pos0 + npos > 0x7fffffff || !sizes_ok(B, m, 1, npos, V))
+    g.qstride = g.pstride = row_stride;
+    if (npos < 1 || pos0 < 0 || (int64_t)pos0 + npos > 0x7fffffff || !sizes_ok(B, m, 1, npos, V) ||
+        !stride_ok(row_stride, V, (int64_t)B * m * npos))
         return ERSD_ERR_INVALID_ARG;
     if (workspace_bytes < workspace_for(g)) return ERSD_ERR_WORKSPACE_TOO_SMALL;
     const int rr = launch_races(nullptr, logits, dt, g, temperature, seed, workspace, workspace_bytes, stream,
@@ -2002,11 +2066,19 @@ int ersd_race_sample(const void* logits, ersd_dtype dt, int32_t B, int32_t m, in
                          workspace, workspace_bytes, stream);
 }
 
+int ersd_race_sample(const void* logits, ersd_dtype dt, int32_t B, int32_t m, int32_t npos, int32_t V, int32_t pos0,
+                     float temperature, uint64_t seed, int32_t* tokens, void* workspace, size_t workspace_bytes,
+                     void* stream) {
+    return ersd_race_sample_strided(logits, V, dt, B, m, npos, V, pos0, temperature, seed, tokens, workspace,
+                                    workspace_bytes, stream);
+}
+
 size_t ersd_race_sample_workspace_bytes(int32_t B, int32_t m, int32_t npos, int32_t V, ersd_dtype dt) {
     if (dt != ERSD_F32 && dt != ERSD_BF16) return 0;
     if (npos < 1 || !sizes_ok(B, m, 1, npos, V)) return 0;
     Geometry g;
     g.B = B; g.m = m; g.kd = 0; g.kt = npos; g.V = V;
+    g.qstride = g.pstride = 0;
     return workspace_for(g);
 }
 

@@ -42,6 +42,21 @@ def lib():
         L.ersd_race_verify_tree.argtypes = [vp, vp, ctypes.c_int, i32, i32, i32, vp, f32, u64,
                                             vp, vp, vp, vp, vp, sz, vp]
         L.ersd_race_verify_tree.restype = ctypes.c_int
+        i64 = ctypes.c_int64
+        L.ersd_race_verify_strided.argtypes = [vp, i64, vp, i64, ctypes.c_int, i32, i32, i32, f32, u64,
+                                               vp, vp, vp, vp, sz, vp]
+        L.ersd_race_verify_strided.restype = ctypes.c_int
+        L.ersd_race_verify_multi_strided.argtypes = [vp, i64, vp, i64, ctypes.c_int, i32, i32, i32, i32, f32, u64,
+                                                     vp, vp, vp, vp, vp, vp, sz, vp]
+        L.ersd_race_verify_multi_strided.restype = ctypes.c_int
+        L.ersd_race_verify_tree_strided.argtypes = [vp, i64, vp, i64, ctypes.c_int, i32, i32, i32, vp, f32, u64,
+                                                    vp, vp, vp, vp, vp, sz, vp]
+        L.ersd_race_verify_tree_strided.restype = ctypes.c_int
+        L.ersd_race_sample_strided.argtypes = [vp, i64, ctypes.c_int, i32, i32, i32, i32, i32, f32, u64, vp, vp, sz, vp]
+        L.ersd_race_sample_strided.restype = ctypes.c_int
+        L.ersd_race_verify_arrival_tree_strided.argtypes = [vp, i64, vp, i64, ctypes.c_int, i32, i32, i32, vp, vp, f32,
+                                                            u64, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.ersd_race_verify_arrival_tree_strided.restype = ctypes.c_int
         L.ersd_race_stage_races.argtypes = [ctypes.c_int, vp, vp, ctypes.c_int, i32, i32, i32, i32, f32, u64, vp, sz, vp]
         L.ersd_race_stage_races.restype = ctypes.c_int
         L.ersd_race_stage_accept.argtypes = [ctypes.c_int, ctypes.c_int, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp,
@@ -116,6 +131,27 @@ def _dev(t, name):
     return t
 
 
+def _rows(t, name):
+    """A logits tensor whose rows may be strided (a padded head, a slice [..., :V]): returns its row stride in
+    elements.  The vocabulary axis must be dense and the leading axes must step through the rows uniformly."""
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU (libersd has no CPU path)")
+    V = t.shape[-1]
+    if V > 1 and t.stride(-1) != 1:
+        raise ValueError(f"{name}: the vocabulary axis must be contiguous")
+    lead = [(n, st) for n, st in zip(t.shape[:-1], t.stride()[:-1]) if n > 1]
+    if not lead:
+        return V
+    stride, span = lead[-1][1], lead[-1][1] * lead[-1][0]
+    for n, st in reversed(lead[:-1]):
+        if st != span:
+            raise ValueError(f"{name}: rows must be evenly strided (got strides {tuple(t.stride())})")
+        span = st * n
+    if stride < V:
+        raise ValueError(f"{name}: rows overlap (row stride {stride} < V {V})")
+    return stride
+
+
 def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
@@ -135,7 +171,8 @@ def _workspace(variant, B, m, k_or_N, V, code, device, workspace):
 
 def race_verify(draft_logits, target_logits, temperature, seed, workspace=None):
     """Sequence variant.  draft [B,k,V], target [B,k+1,V] -> (draft_tokens [B,k], target_tokens [B,k+1], accept_len [B])."""
-    d, t = _dev(draft_logits, "draft_logits"), _dev(target_logits, "target_logits")
+    d, t = draft_logits, target_logits
+    ds, ts = _rows(d, "draft_logits"), _rows(t, "target_logits")
     code = _dtype_code(d)
     if _dtype_code(t) != code:
         raise TypeError("draft and target logits must share a dtype")
@@ -146,14 +183,16 @@ def race_verify(draft_logits, target_logits, temperature, seed, workspace=None):
     ttok = torch.empty((B, k + 1), dtype=torch.int32, device=d.device)
     acc = torch.empty((B,), dtype=torch.int32, device=d.device)
     ws, ws_bytes = _workspace(VARIANT_SEQUENCE, B, 1, k, V, code, d.device, workspace)
-    _check(lib().ersd_race_verify(d.data_ptr(), t.data_ptr(), code, B, k, V, float(temperature), int(seed),
-                                  dtok.data_ptr(), ttok.data_ptr(), acc.data_ptr(), ws.data_ptr(), ws_bytes, _stream()))
+    _check(lib().ersd_race_verify_strided(d.data_ptr(), ds, t.data_ptr(), ts, code, B, k, V, float(temperature),
+                                          int(seed), dtok.data_ptr(), ttok.data_ptr(), acc.data_ptr(), ws.data_ptr(),
+                                          ws_bytes, _stream()))
     return dtok, ttok, acc
 
 
 def race_verify_multi(draft_logits, target_logits, temperature, seed, workspace=None):
     """draft [B,m,k,V], target [B,m,k+1,V] -> (draft_tokens, target_tokens, accept_len [B,m], best_draft [B], best_len [B])."""
-    d, t = _dev(draft_logits, "draft_logits"), _dev(target_logits, "target_logits")
+    d, t = draft_logits, target_logits
+    ds, ts = _rows(d, "draft_logits"), _rows(t, "target_logits")
     code = _dtype_code(d)
     if _dtype_code(t) != code:
         raise TypeError("draft and target logits must share a dtype")
@@ -167,15 +206,17 @@ def race_verify_multi(draft_logits, target_logits, temperature, seed, workspace=
     bd = torch.empty((B,), dtype=torch.int32, device=dev)
     bl = torch.empty((B,), dtype=torch.int32, device=dev)
     ws, ws_bytes = _workspace(VARIANT_MULTI, B, m, k, V, code, dev, workspace)
-    _check(lib().ersd_race_verify_multi(d.data_ptr(), t.data_ptr(), code, B, m, k, V, float(temperature), int(seed),
-                                        dtok.data_ptr(), ttok.data_ptr(), acc.data_ptr(), bd.data_ptr(), bl.data_ptr(),
-                                        ws.data_ptr(), ws_bytes, _stream()))
+    _check(lib().ersd_race_verify_multi_strided(d.data_ptr(), ds, t.data_ptr(), ts, code, B, m, k, V,
+                                                float(temperature), int(seed), dtok.data_ptr(), ttok.data_ptr(),
+                                                acc.data_ptr(), bd.data_ptr(), bl.data_ptr(), ws.data_ptr(), ws_bytes,
+                                                _stream()))
     return dtok, ttok, acc, bd, bl
 
 
 def race_verify_tree(draft_logits, target_logits, parent, temperature, seed, workspace=None):
     """draft, target [B,N,V]; parent int32 [N] on the GPU -> (draft_tokens, target_tokens [B,N], accept_len [B], accept_node [B])."""
-    d, t = _dev(draft_logits, "draft_logits"), _dev(target_logits, "target_logits")
+    d, t = draft_logits, target_logits
+    ds, ts = _rows(d, "draft_logits"), _rows(t, "target_logits")
     p = _dev(parent, "parent")
     code = _dtype_code(d)
     if _dtype_code(t) != code:
@@ -191,16 +232,17 @@ def race_verify_tree(draft_logits, target_logits, parent, temperature, seed, wor
     acc = torch.empty((B,), dtype=torch.int32, device=dev)
     node = torch.empty((B,), dtype=torch.int32, device=dev)
     ws, ws_bytes = _workspace(VARIANT_TREE, B, 1, N, V, code, dev, workspace)
-    _check(lib().ersd_race_verify_tree(d.data_ptr(), t.data_ptr(), code, B, N, V, p.data_ptr(), float(temperature),
-                                       int(seed), dtok.data_ptr(), ttok.data_ptr(), acc.data_ptr(), node.data_ptr(),
-                                       ws.data_ptr(), ws_bytes, _stream()))
+    _check(lib().ersd_race_verify_tree_strided(d.data_ptr(), ds, t.data_ptr(), ts, code, B, N, V, p.data_ptr(),
+                                               float(temperature), int(seed), dtok.data_ptr(), ttok.data_ptr(),
+                                               acc.data_ptr(), node.data_ptr(), ws.data_ptr(), ws_bytes, _stream()))
     return dtok, ttok, acc, node
 
 
 def race_sample(logits, pos0, temperature, seed, workspace=None):
     """One model's races.  logits [B,m,npos,V] on the GPU -> tokens [B,m,npos]; race (b,d,j) is the race of
     position pos0 + j (the drafting step, or 0 when a whole target tensor is raced)."""
-    x = _dev(logits, "logits")
+    x = logits
+    xs = _rows(x, "logits")
     code = _dtype_code(x)
     B, m, npos, V = x.shape
     need = int(lib().ersd_race_sample_workspace_bytes(B, m, npos, V, code))
@@ -208,8 +250,9 @@ def race_sample(logits, pos0, temperature, seed, workspace=None):
         raise ErsdError(-2, status_string(-2))
     ws = workspace if workspace is not None else torch.empty(need, dtype=torch.uint8, device=x.device)
     tok = torch.empty((B, m, npos), dtype=torch.int32, device=x.device)
-    _check(lib().ersd_race_sample(x.data_ptr(), code, B, m, npos, V, int(pos0), float(temperature), int(seed),
-                                  tok.data_ptr(), ws.data_ptr(), ws.numel() * ws.element_size(), _stream()))
+    _check(lib().ersd_race_sample_strided(x.data_ptr(), xs, code, B, m, npos, V, int(pos0), float(temperature),
+                                          int(seed), tok.data_ptr(), ws.data_ptr(), ws.numel() * ws.element_size(),
+                                          _stream()))
     return tok
 
 
@@ -365,7 +408,8 @@ def race_verify_arrival_tree(draft_logits, target_logits, parent, rank, temperat
 
     -> (draft_tokens [B,N], target_tokens [B,N+1], accept_len [B], accept_node [B], emitted [B,N+1])
     """
-    d, t = _dev(draft_logits, "draft_logits"), _dev(target_logits, "target_logits")
+    d, t = draft_logits, target_logits
+    ds, ts = _rows(d, "draft_logits"), _rows(t, "target_logits")
     par, rk = _dev(parent, "parent"), _dev(rank, "rank")
     code = _dtype_code(d)
     if _dtype_code(t) != code:
@@ -386,11 +430,11 @@ def race_verify_arrival_tree(draft_logits, target_logits, parent, rank, temperat
     acc = torch.empty((B,), dtype=torch.int32, device=d.device)
     node = torch.empty((B,), dtype=torch.int32, device=d.device)
     emitted = torch.empty((B, C), dtype=torch.int32, device=d.device)
-    _check(lib().ersd_race_verify_arrival_tree(d.data_ptr(), t.data_ptr(), code, B, N, V, par.data_ptr(), rk.data_ptr(),
-                                               float(temperature), int(seed), dtok.data_ptr(), ttok.data_ptr(),
-                                               acc.data_ptr(), node.data_ptr(), emitted.data_ptr(),
-                                               workspace.data_ptr(), workspace.numel() * workspace.element_size(),
-                                               _stream()))
+    _check(lib().ersd_race_verify_arrival_tree_strided(d.data_ptr(), ds, t.data_ptr(), ts, code, B, N, V,
+                                                       par.data_ptr(), rk.data_ptr(), float(temperature), int(seed),
+                                                       dtok.data_ptr(), ttok.data_ptr(), acc.data_ptr(),
+                                                       node.data_ptr(), emitted.data_ptr(), workspace.data_ptr(),
+                                                       workspace.numel() * workspace.element_size(), _stream()))
     return dtok, ttok, acc, node, emitted
 
 

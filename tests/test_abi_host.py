@@ -214,3 +214,52 @@ def test_tree_builders_argument_errors(L):
     assert L.ersd_tree_build_specinfer_host(0, 2, 3, par, rk) == -2
     assert L.ersd_tree_build_specinfer_host(4, -1, 3, par, rk) == -2
     assert L.ersd_tree_build_specinfer_host(4, 2, 0, par, rk) == -2
+
+
+def test_strided_argument_errors(L):
+    """Row strides are checked on the host: rows must not overlap and the tensors must stay addressable."""
+    def seq(ds=64, ts=64, V=64, **kw):
+        a = dict(d=FAKE, t=FAKE, dt=0, B=1, k=2, T=1.0, seed=0, o1=FAKE, o2=FAKE, o3=FAKE, ws=FAKE, wsb=1 << 30)
+        a.update(kw)
+        return L.ersd_race_verify_strided(a["d"], ds, a["t"], ts, a["dt"], a["B"], a["k"], V, a["T"], a["seed"],
+                                          a["o1"], a["o2"], a["o3"], a["ws"], a["wsb"], None)
+    assert seq(ds=63) == -2 and seq(ts=63) == -2 and seq(ds=0) == -2 and seq(ts=-64) == -2
+    assert seq(ds=1 << 41) == -2                      # beyond what the row offsets are sized for
+    assert seq(d=None) == -1 and seq(o3=None) == -1 and seq(dt=5) == -3 and seq(T=0.0) == -2
+    assert seq(ds=72, ts=64, wsb=16) == -5            # valid strides reach the workspace check
+    assert L.ersd_race_verify_multi_strided(FAKE, 63, FAKE, 64, 0, 1, 2, 2, 64, 1.0, 0, FAKE, FAKE, FAKE, FAKE, FAKE,
+                                            FAKE, 1 << 30, None) == -2
+    assert L.ersd_race_verify_multi_strided(FAKE, 64, FAKE, 64, 0, 1, 2, 2, 64, 1.0, 0, FAKE, FAKE, FAKE, None, FAKE,
+                                            FAKE, 1 << 30, None) == -1
+    assert L.ersd_race_verify_tree_strided(FAKE, 64, FAKE, 32, 0, 1, 3, 64, FAKE, 1.0, 0, FAKE, FAKE, FAKE, FAKE,
+                                           FAKE, 1 << 30, None) == -2
+    assert L.ersd_race_verify_tree_strided(FAKE, 64, FAKE, 64, 0, 1, 3, 64, None, 1.0, 0, FAKE, FAKE, FAKE, FAKE,
+                                           FAKE, 1 << 30, None) == -1
+    assert L.ersd_race_sample_strided(FAKE, 10, 0, 1, 1, 2, 64, 0, 1.0, 0, FAKE, FAKE, 1 << 30, None) == -2
+    assert L.ersd_race_sample_strided(FAKE, 64, 0, 1, 1, 2, 64, 0, 1.0, 0, None, FAKE, 1 << 30, None) == -1
+    assert L.ersd_race_verify_arrival_tree_strided(FAKE, 64, FAKE, 63, 0, 1, 3, 64, FAKE, FAKE, 1.0, 0, FAKE, FAKE,
+                                                   FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == -2
+
+
+def test_binding_row_stride_of_views():
+    """The binding derives the row stride from a tensor's shape and strides alone."""
+    import torch
+    from paper_2504_15475_amd import race
+
+    class View:  # shape and strides of a tensor, flagged as device memory
+        def __init__(self, t):
+            self.shape, self._s, self.is_cuda = t.shape, t.stride(), True
+
+        def stride(self, i=None):
+            return self._s if i is None else self._s[i]
+
+    x = torch.zeros(3, 4, 40, device="meta")
+    assert race._rows(View(x), "x") == 40
+    assert race._rows(View(x[..., :33]), "x") == 40          # padded vocabulary
+    assert race._rows(View(x[:1, :3, :33]), "x") == 40       # a single leading block keeps rows evenly spaced
+    with pytest.raises(ValueError):
+        race._rows(View(x[:, :3, :33]), "x")                 # a cut middle axis does not
+    with pytest.raises(ValueError):
+        race._rows(View(x[..., ::2]), "x")                   # vocabulary axis not dense
+    y = torch.zeros(5, 64, device="meta").unsqueeze(0)
+    assert race._rows(View(y[..., :50]), "y") == 64
