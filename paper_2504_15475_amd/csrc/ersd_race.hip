@@ -2161,6 +2161,6 @@ const char* ersd_status_string(int status) {
 
 int ersd_philox_rounds(void) { return kPhiloxRounds; }
 
-int ersd_version(void) { return 400; }
+int ersd_version(void) { return 410; }
 
 }  // extern "C"
