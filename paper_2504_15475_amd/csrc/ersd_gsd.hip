@@ -19,38 +19,19 @@
 #include <cstdint>
 
 #include "ersd.h"
+#include "ersd_philox.h"
 
 namespace {
+
+using ersd_philox::philox4x32;
 
 constexpr int kThreads = 256;
 constexpr int kWave = 64;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kListCap = 512;
-#ifndef ERSD_PHILOX_ROUNDS
-#define ERSD_PHILOX_ROUNDS 7
-#endif
-constexpr int kPhiloxRounds = ERSD_PHILOX_ROUNDS;
 constexpr float kNone = -3.0e38f;  // "no value yet": below every finite score, but finite so that differences are defined
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ void philox4x32(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1,
-                                              uint32_t out[4]) {
-#pragma unroll
-    for (int r = 0; r < kPhiloxRounds; ++r) {
-        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
-        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
-        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
-        c1 = (uint32_t)p1;
-        c3 = (uint32_t)p0;
-        c0 = n0;
-        c2 = n2;
-        k0 += 0x9E3779B9u;
-        k1 += 0xBB67AE85u;
-    }
-    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
-}
 
 __device__ __forceinline__ float widen(const char* row, int dt, int32_t i) {
     if (dt == ERSD_F32) return reinterpret_cast<const float*>(row)[i];

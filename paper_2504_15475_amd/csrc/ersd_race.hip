@@ -37,8 +37,13 @@
 #include <cstring>
 
 #include "ersd.h"
+#include "ersd_partition.h"
+#include "ersd_philox.h"
 
 namespace {
+
+using namespace ersd_part;
+using namespace ersd_philox;
 
 #ifndef ERSD_THREADS
 #define ERSD_THREADS 256
@@ -54,20 +59,7 @@ constexpr int kStages = ERSD_STAGES;                // register buffers per row:
 constexpr int kListCap = 512;                       // candidate slots per side per workgroup
 constexpr int kWave = 64;
 constexpr int kWaves = kThreads / kWave;
-#ifndef ERSD_W_PAIR
-#define ERSD_W_PAIR 10
-#define ERSD_W_SINGLE 7
-#endif
-constexpr uint32_t kWPair = ERSD_W_PAIR, kWSingle = ERSD_W_SINGLE;  // relative cost of one group in a pair row / target-only row
-constexpr uint64_t kMinQuota = 64 * kWPair * 16;     // cost units a workgroup gets at least (16 pair iterations of a wave)
 constexpr uint32_t kMaxBlocks = 256 * 16;           // upper bound of resident workgroups, for workspace sizing
-
-#ifndef ERSD_PHILOX_ROUNDS
-#define ERSD_PHILOX_ROUNDS 7
-#endif
-constexpr int kPhiloxRounds = ERSD_PHILOX_ROUNDS;   // 7 by default; 10 is the generator's standard strength
-constexpr uint32_t kPhiloxM0 = 0xD2511F53u, kPhiloxM1 = 0xCD9E8D57u;
-constexpr uint32_t kPhiloxW0 = 0x9E3779B9u, kPhiloxW1 = 0xBB67AE85u;
 
 constexpr int kMaxSurvivors = 4;
 constexpr int kMaxRank = ERSD_MAX_RANK;             // arrivals of one race a tree may use (Algorithm 5's child ranks)
@@ -92,155 +84,6 @@ struct SegOutArr {   // the same for a draft row of which the first arrivals (no
     Cand c[kMaxArrSurvivors];
 };
 
-// Balanced partition of the concatenated rows (in 8-token groups) over G workgroups.  Shared by the race
-// kernel (which part is mine, which slot do I write) and the finishing kernel (which slots does a row have).
-struct Part {
-    uint64_t U;           // total cost units
-    uint64_t Us;          // cost units per sequence
-    uint64_t pair_units;  // cost units of the pair rows of one sequence
-    uint64_t rows;        // target rows = races
-    uint32_t V8;          // groups per row
-    uint32_t kd, kt;      // draft rows / target rows per sequence
-    uint32_t G;           // workgroups
-    uint32_t nslot;       // partial slots per (row, side)
-    // Every workgroup works out its share before its first load, and integer division is a long instruction
-    // sequence on this hardware.  When all cost units fit in 32 bits (fast != 0) the quotients below are taken by
-    // multiplication with reciprocals prepared on the host (see magic_of); otherwise by plain 64-bit division.
-    uint32_t fast;
-    uint32_t q, r;        // U / G and U % G: share b starts at unit b * q + (b * r) / G = floor(b * U / G)
-    uint64_t m_G, m_q, m_Us, m_pair_row, m_single_row, m_kt;  // reciprocals of G, q, Us, kWPair*V8, kWSingle*V8, kt
-    // Arrival trees: which contexts have a draft row is known on the device only.  wprefix[c] = summed weights of
-    // the contexts before c (kt + 1 entries, device memory); nullptr for the closed-form layouts above.
-    const uint32_t* wprefix;
-};
-
-// Division of a 32-bit number by a fixed 32-bit divisor d through its 64-bit reciprocal m = floor(2^64 / d) + 1:
-// floor(n / d) = floor(n * m / 2^64) for every n < 2^32 (the product overshoots n / d by less than 2^-32, which
-// cannot reach the next integer because the fraction of n / d is at most 1 - 1/d).  m == 0 stands for d == 1.
-inline uint64_t magic_of(uint64_t d) { return d <= 1 ? 0 : ~(uint64_t)0 / d + 1; }
-__host__ __device__ inline uint32_t magic_div(uint32_t n, uint64_t m) {
-    if (!m) return n;
-    const uint64_t lo = (uint64_t)n * (uint32_t)m, hi = (uint64_t)n * (uint32_t)(m >> 32);
-    return (uint32_t)((hi + (lo >> 32)) >> 32);
-}
-
-// context whose cost units contain weighted position wpos (in units of one group): largest c with wprefix[c] <= wpos
-__host__ __device__ inline uint32_t part_table_row(const Part& p, uint64_t wpos) {
-    uint32_t lo = 0, hi = p.kt;  // answer in [lo, hi)
-    while (hi - lo > 1) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if ((uint64_t)p.wprefix[mid] <= wpos) lo = mid;
-        else hi = mid;
-    }
-    return lo;
-}
-
-struct PartPos {
-    uint64_t row;   // global row = seq * kt + j
-    uint64_t seq;
-    uint32_t j;     // row within the sequence
-    uint32_t grp;   // group within the row
-};
-
-// group that contains cost unit u (u >= U: the end)
-__host__ __device__ inline PartPos part_unit_to_pos(const Part& p, uint64_t u) {
-    PartPos o;
-    if (u >= p.U) {
-        o.row = p.rows;
-        o.seq = p.fast ? magic_div((uint32_t)p.rows, p.m_kt) : p.rows / p.kt;
-        o.j = 0;
-        o.grp = 0;
-        return o;
-    }
-    if (p.fast) {  // closed-form layout, everything below 2^32
-        const uint32_t u32 = (uint32_t)u, seq = magic_div(u32, p.m_Us), rem = u32 - seq * (uint32_t)p.Us;
-        o.seq = seq;
-        if (rem < (uint32_t)p.pair_units) {
-            o.j = magic_div(rem, p.m_pair_row);
-            o.grp = (rem - o.j * (kWPair * p.V8)) / kWPair;
-        } else {
-            const uint32_t r2 = rem - (uint32_t)p.pair_units, jj = magic_div(r2, p.m_single_row);
-            o.j = p.kd + jj;
-            o.grp = (r2 - jj * (kWSingle * p.V8)) / kWSingle;
-        }
-        o.row = (uint64_t)seq * p.kt + o.j;
-        return o;
-    }
-    const uint64_t seq = u / p.Us, rem = u % p.Us;
-    uint64_t row, grp;
-    if (p.wprefix) {
-        row = part_table_row(p, rem / p.V8);
-        grp = (rem - (uint64_t)p.wprefix[row] * p.V8) / (p.wprefix[row + 1] - p.wprefix[row]);
-    } else if (rem < p.pair_units) {
-        row = rem / ((uint64_t)kWPair * p.V8);
-        grp = (rem % ((uint64_t)kWPair * p.V8)) / kWPair;
-    } else {
-        const uint64_t r2 = rem - p.pair_units;
-        row = p.kd + r2 / ((uint64_t)kWSingle * p.V8);
-        grp = (r2 % ((uint64_t)kWSingle * p.V8)) / kWSingle;
-    }
-    o.seq = seq;
-    o.j = (uint32_t)row;
-    o.grp = (uint32_t)grp;
-    o.row = seq * p.kt + row;
-    return o;
-}
-// first cost unit of workgroup b's share, floor(b * U / G); b == G gives U
-__host__ __device__ inline uint64_t part_block_start_unit(const Part& p, uint32_t b) {
-    if (p.fast) return (uint64_t)(b * p.q + magic_div(b * p.r, p.m_G));  // b * r < G^2 <= 2^24; the sum is <= U
-    return (uint64_t)b * p.U / p.G;
-}
-// first group of workgroup b's share; b == G gives the end
-__host__ __device__ inline PartPos part_start_pos(const Part& p, uint32_t b) {
-    return part_unit_to_pos(p, part_block_start_unit(p, b));
-}
-// first cost unit and weight of row (seq, j)
-__host__ __device__ inline uint64_t part_row_unit(const Part& p, uint64_t seq, uint32_t j, uint32_t* w) {
-    if (p.wprefix) {
-        *w = p.wprefix[j + 1] - p.wprefix[j];
-        return seq * p.Us + (uint64_t)p.wprefix[j] * p.V8;
-    }
-    *w = j < p.kd ? kWPair : kWSingle;
-    return seq * p.Us + (j < p.kd ? (uint64_t)j * kWPair * p.V8 : p.pair_units + (uint64_t)(j - p.kd) * kWSingle * p.V8);
-}
-// workgroup whose share contains cost unit x < U: the largest b with floor(b * U / G) <= x
-__host__ __device__ inline uint32_t part_block_of_unit(const Part& p, uint64_t x) {
-    if (p.fast) {
-        // b * q <= floor(b * U / G) < b * q + G and q > G (the quota), so the answer is floor(x / q) or one less
-        const uint32_t b = magic_div((uint32_t)x, p.m_q);
-        if (b >= p.G) return p.G - 1;
-        return part_block_start_unit(p, b) <= x ? b : b - 1;
-    }
-    return (uint32_t)(((x + 1) * p.G - 1) / p.U);
-}
-// workgroup that holds the first group of row (seq, j): a share starts at the group that contains its first unit,
-// so a group belongs to the last share that starts at or before the group's last unit
-__host__ __device__ inline uint32_t part_first_block(const Part& p, uint64_t seq, uint32_t j) {
-    uint32_t w;
-    const uint64_t u0 = part_row_unit(p, seq, j, &w);
-    return part_block_of_unit(p, u0 + w - 1);
-}
-// workgroup that holds the last group of row (seq, j)
-__host__ __device__ inline uint32_t part_last_block(const Part& p, uint64_t seq, uint32_t j) {
-    uint32_t w;
-    const uint64_t u1 = part_row_unit(p, seq, j, &w) + (uint64_t)w * p.V8;
-    return part_block_of_unit(p, u1 - 1);
-}
-// number of segment slots of a global row
-__host__ __device__ inline uint32_t part_row_slots(const Part& p, uint64_t row) {
-    uint64_t seq;
-    uint32_t j;
-    if (p.fast) {
-        const uint32_t s32 = magic_div((uint32_t)row, p.m_kt);
-        seq = s32;
-        j = (uint32_t)row - s32 * p.kt;
-    } else {
-        seq = row / p.kt;
-        j = (uint32_t)(row % p.kt);
-    }
-    return part_last_block(p, seq, j) - part_first_block(p, seq, j) + 1;
-}
-
 struct RaceArgs {
     const char* draft;
     const char* target;
@@ -259,31 +102,6 @@ struct RaceArgs {
     SegOutArr* outq;       // [row][slot]: draft-side survivors
     const int32_t* need;   // [kt]: arrivals wanted per context (0: the context has no child, its draft row is not read)
 };
-
-// ------------------------------------------------------------------------------------------ Philox4x32-R
-__device__ __forceinline__ void philox4x32(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
-                                              uint32_t k0, uint32_t k1, uint32_t out[4]) {
-#pragma unroll
-    for (int r = 0; r < kPhiloxRounds; ++r) {
-        const uint64_t p0 = (uint64_t)kPhiloxM0 * c0;
-        const uint64_t p1 = (uint64_t)kPhiloxM1 * c2;
-        uint32_t n0, n2;
-        if (r >= 2) {  // gfx950's three-input bitwise operation (truth table 0x96 = a ^ b ^ c): one instruction each
-            n0 = __builtin_amdgcn_bitop3_b32((uint32_t)(p1 >> 32), c1, k0, 0x96);
-            n2 = __builtin_amdgcn_bitop3_b32((uint32_t)(p0 >> 32), c3, k1, 0x96);
-        } else {       // in the first two rounds most operands are wavefront-uniform: left to the scalar unit
-            n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-            n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
-        }
-        c1 = (uint32_t)p1;
-        c3 = (uint32_t)p0;
-        c0 = n0;
-        c2 = n2;
-        k0 += kPhiloxW0;
-        k1 += kPhiloxW1;
-    }
-    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
-}
 
 // ------------------------------------------------------------------------------------------ exact score
 // The definition, in double precision: v = (x + 1/2) 2^-32, e = -log1p(-v), score = logit/T - ln e.
