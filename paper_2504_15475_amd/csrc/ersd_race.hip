@@ -1219,7 +1219,7 @@ __device__ int32_t resolve_row(const SegOut* o, uint32_t nslots, double T, bool 
     if (have)  // fp32 cannot tell: score the contenders exactly
         for (uint32_t s = lane8; s < nslots; s += 8) {
             const SegOut so = s == (uint32_t)lane8 ? mine : o[s];
-            for (int32_t k = 0; k < so.count; ++k) {
+            for (int32_t k = 0; k < so.count && k < kMaxSurvivors; ++k) {  // never past the record, whatever it holds
                 const Cand cd = so.c[k];
                 if (cd.s2 + refine_err(cd.s2) >= lstar) {
                     const double sc = exact_score(cd.logit, T, cd.word);
