@@ -147,3 +147,30 @@ def test_trees_from_the_builders_verify_like_the_oracle(race, oracle_mod):
     for parent, rank in ((opt_parent, opt_rank), (si_parent, si_rank)):
         draft, target = small_inputs(3, len(parent), 32768, torch.bfloat16, 41, noise=0.4)
         run(race, oracle_mod, draft, target, parent, rank, 1.0, 8, note="builder tree")
+
+
+@pytest.mark.parametrize("N,shape", [(2048, "bushy"), (2049, "bushy"), (8192, "bushy"), (3000, "chain")])
+def test_largest_trees(race, oracle_mod, N, shape):
+    """The node limit (8192), both sides of the size up to which the tree is staged in LDS (2048), and a walk that
+    is thousands of contexts long."""
+    rng = np.random.default_rng(N)
+    if shape == "chain":
+        parent = np.arange(-1, N - 1, dtype=np.int32)
+        rank = np.zeros(N, dtype=np.int32)
+    else:
+        parent = np.array([int(rng.integers(max(-1, n - 40), n)) for n in range(N)], dtype=np.int32)
+        rank = np.zeros(N, dtype=np.int32)
+        seen = {}
+        for n in range(N):
+            r = seen.get(int(parent[n]), 0)
+            rank[n] = min(r, race.max_rank() - 1)        # a ninth sibling repeats rank 7 and is thereby invalid
+            seen[int(parent[n])] = r + 1
+    B, V = 2, 40
+    g = torch.Generator(device="cuda")
+    g.manual_seed(N)
+    target = 2.0 * torch.randn((B, N + 1, V), generator=g, device="cuda")
+    noise = 0.05 if shape == "chain" else 0.6                 # close models: the chain is followed far down
+    draft = target + noise * torch.randn((B, N + 1, V), generator=g, device="cuda")
+    gpu, ora, ex = run(race, oracle_mod, draft.contiguous(), target.contiguous(), parent, rank, 1.0, 11, note=f"{shape} N={N}")
+    if shape == "chain":
+        assert int(ora["accept_len"].max()) > 5

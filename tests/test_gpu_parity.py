@@ -306,3 +306,12 @@ def test_vocabulary_smaller_than_a_group_and_gpt2_size(race, oracle_mod):
     for V in (1, 2, 5, 7):
         run_case(race, oracle_mod, wl.shrink(wl.WORKLOADS[0], B=4, k=2, V=V), note="no whole group")
     run_case(race, oracle_mod, wl.shrink(wl.WORKLOADS[1], B=8, k=4, V=50257), note="odd vocabulary at full row length")
+
+
+def test_long_sequences_many_drafts_and_big_trees(race, oracle_mod):
+    """Shapes far from the benchmark's: thousands of positions, hundreds of drafts, thousands of tree nodes, each
+    with a small vocabulary (many rows per workgroup, and the two-launch finishing path)."""
+    run_case(race, oracle_mod, wl.shrink(wl.WORKLOADS[0], B=2, k=3000, V=24), note="k = 3000")
+    run_case(race, oracle_mod, wl.shrink(wl.WORKLOADS[3], B=2, m=300, k=3, V=40), note="m = 300")
+    run_case(race, oracle_mod, wl.shrink(wl.WORKLOADS[4], B=2, N=5000, V=16), note="N = 5000")
+    run_case(race, oracle_mod, wl.shrink(wl.WORKLOADS[1], B=3000, k=1, V=8), note="B = 3000")
