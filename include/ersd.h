@@ -319,7 +319,7 @@ int ersd_max_rank(void);
  * Device self-check of the two single-precision bounds the streaming filter relies on, over all 2^32
  * generator words, against double precision.  counters: DEVICE array of 4 uint64, written as
  *   [0] words whose cheap upper bound of -log2 e fell below the true value      (must be 0)
- *   [1] words whose refined log2 e is off by more than 2^-7                    (must be 0)
+ *   [1] words whose refined log2 e is off by more than 2^-9                    (must be 0)
  *   [2] largest refinement error, [3] largest upper-bound slack (IEEE fp32 bit patterns)
  * Enqueues on `stream`; takes a fraction of a second.
  */

@@ -65,7 +65,7 @@ def test_filter_bounds_hold_for_every_generator_word(race):
     r = race.selftest_bounds()
     print(r, flush=True)
     assert r["bad_upper"] == 0 and r["bad_refine"] == 0
-    assert r["max_refine_err"] <= 2.0 ** -7
+    assert r["max_refine_err"] <= 2.0 ** -9
 
 
 SMALL = [
