@@ -22,7 +22,7 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per race-kernel launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a copy
 # kernel of known size; filled in from the summaries under profiles/ (None = not measured for that workload).
-MEASURED_TRAFFIC_BYTES = {1: 286224930, 2: 5177820193, 3: 1118954679, 4: 1068131359}
+MEASURED_TRAFFIC_BYTES = {1: 286262270, 2: 5171172134, 3: 1118971385, 4: 1068091931}
 
 
 def main():
