@@ -126,6 +126,24 @@ def main():
                     "kernel_ms_min": round(durs[0], 5), "kernel_ms_median": round(durs[len(durs) // 2], 5),
                     "algorithmic_bytes_per_launch": algo_bytes}
 
+    if roofline is not None:
+        # context, outside the timed region: the same tensors read once by a kernel that does nothing else, with the
+        # race kernel's loads and launch shape
+        sink = torch.zeros(1, dtype=torch.int32, device=dev)
+        n_probe = 24
+        pe = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_probe)]
+        for i in range(4):
+            race.read_probe(sets[i % len(sets)]["draft"], sets[i % len(sets)]["target"], sink)
+        for i, (e0, e1) in enumerate(pe):
+            e0.record()
+            race.read_probe(sets[i % len(sets)]["draft"], sets[i % len(sets)]["target"], sink)
+            e1.record()
+        torch.cuda.synchronize()
+        probe_ms = sum(e0.elapsed_time(e1) for e0, e1 in pe) / n_probe
+        roofline["plain_read_same_shape"] = {"ms": round(probe_ms, 5),
+                                             "GB/s": round(algo_bytes / (probe_ms * 1e-3) / 1e9, 1),
+                                             "race_kernel_vs_plain_read": round(probe_ms / kernel_ms, 4)}
+
     out = {
         "metric": "race_elements_per_sec", "value": value, "unit": "elements/s", "n_gpus": 1, "steps": K,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",

@@ -325,6 +325,14 @@ int ersd_max_rank(void);
  */
 int ersd_selftest_bounds(uint64_t* counters, void* stream);
 
+/*
+ * Measurement aid: reads the device buffers a and b (b may be NULL with b_bytes 0) exactly once with the race
+ * kernel's load instructions and launch shape and does nothing else, so that a benchmark can print what the memory
+ * system gives a kernel of this shape beside the race kernel's own rate.  Sizes are multiples of 16 bytes, the
+ * buffers 16-byte aligned; sink is a DEVICE uint32 that is practically never written.  Enqueues on `stream`.
+ */
+int ersd_read_probe(const void* a, size_t a_bytes, const void* b, size_t b_bytes, void* sink, void* stream);
+
 /* Host helper: 1 if parent[0..N) (a HOST array) satisfies the tree contract above, else 0. */
 int ersd_tree_validate_host(const int32_t* parent_host, int32_t N);
 

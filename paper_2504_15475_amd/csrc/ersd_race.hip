@@ -1378,6 +1378,29 @@ __global__ void __launch_bounds__(kThreads) selftest_bounds_kernel(unsigned long
     atomicMax(&counters[3], (unsigned long long)__float_as_uint(max_slack));
 }
 
+// Reads two buffers once with the race kernel's loads and launch shape and nothing else: what the memory system
+// delivers to a kernel of this shape, for the benchmark to print beside the race kernel's rate.
+__global__ void __launch_bounds__(kThreads) read_probe_kernel(const u32x4* a, uint64_t na, const u32x4* b, uint64_t nb,
+                                                              uint32_t* sink) {
+    const uint64_t n = na + nb, per = (n + gridDim.x - 1) / gridDim.x;
+    const uint64_t lo = per * blockIdx.x, hi = lo + per < n ? lo + per : n;
+    u32x4 acc = {0, 0, 0, 0};
+    constexpr int kUnroll = 4;
+    uint64_t i = lo + threadIdx.x;
+    for (; i + (kUnroll - 1) * kThreads < hi; i += (uint64_t)kUnroll * kThreads) {
+        u32x4 v[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const uint64_t t = i + (uint64_t)u * kThreads;
+            v[u] = __builtin_nontemporal_load(t < na ? a + t : b + (t - na));
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) acc ^= v[u];
+    }
+    for (; i < hi; i += kThreads) acc ^= __builtin_nontemporal_load(i < na ? a + i : b + (i - na));
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) sink[0] = 1;  // keeps the loads; practically never true
+}
+
 __global__ void zero_counters_kernel(unsigned long long* counters) {
     if (threadIdx.x < 4) counters[threadIdx.x] = 0;
 }
@@ -1926,6 +1949,18 @@ int ersd_accept_lengths(int variant, int32_t B, int32_t m, int32_t k_or_N, const
     f.best_len = variant == ERSD_VARIANT_MULTI ? best_len : nullptr;
     f.accept_node = variant == ERSD_VARIANT_TREE ? accept_node : nullptr;
     hipLaunchKernelGGL(accept_kernel, dim3((uint32_t)g.B), dim3(kThreads), 0, static_cast<hipStream_t>(stream), f);
+    return hipGetLastError() == hipSuccess ? ERSD_OK : ERSD_ERR_HIP;
+}
+
+int ersd_read_probe(const void* a, size_t a_bytes, const void* b, size_t b_bytes, void* sink, void* stream) {
+    if (!a || !sink || (b_bytes && !b)) return ERSD_ERR_NULL_POINTER;
+    if (((uintptr_t)a & 15) || ((uintptr_t)b & 15) || ((uintptr_t)sink & 3)) return ERSD_ERR_MISALIGNED;
+    if ((a_bytes & 15) || (b_bytes & 15) || a_bytes == 0) return ERSD_ERR_INVALID_ARG;
+    const int blocks = race_blocks(ERSD_BF16);
+    if (blocks < 1) return ERSD_ERR_HIP;
+    hipLaunchKernelGGL(read_probe_kernel, dim3((uint32_t)blocks), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const u32x4*>(a), (uint64_t)(a_bytes / 16), static_cast<const u32x4*>(b),
+                       (uint64_t)(b_bytes / 16), static_cast<uint32_t*>(sink));
     return hipGetLastError() == hipSuccess ? ERSD_OK : ERSD_ERR_HIP;
 }
 

@@ -86,6 +86,8 @@ def lib():
         L.ersd_tree_build_optimal_host.restype = ctypes.c_int
         L.ersd_tree_build_specinfer_host.argtypes = [i32, i32, i32, vp, vp]
         L.ersd_tree_build_specinfer_host.restype = ctypes.c_int
+        L.ersd_read_probe.argtypes = [vp, sz, vp, sz, vp, vp]
+        L.ersd_read_probe.restype = ctypes.c_int
         L.ersd_selftest_bounds.argtypes = [vp, vp]
         L.ersd_selftest_bounds.restype = ctypes.c_int
         L.ersd_tree_validate_host.argtypes = [vp, i32]
@@ -363,6 +365,19 @@ class PreparedVerify:
                                         p(self.best_draft), p(self.best_len), p(self.accept_node), p(self.workspace),
                                         self.ws_bytes, st))
         return self.outputs()
+
+
+def read_probe(a, b=None, sink=None):
+    """Enqueue one plain read of tensor a (and b) with the race kernel's loads and launch shape (measurement aid)."""
+    _dev(a, "a")
+    if b is not None:
+        _dev(b, "b")
+    if sink is None:
+        sink = torch.zeros(1, dtype=torch.int32, device=a.device)
+    nbytes = lambda t: t.numel() * t.element_size()
+    _check(lib().ersd_read_probe(a.data_ptr(), nbytes(a), None if b is None else b.data_ptr(),
+                                 0 if b is None else nbytes(b), sink.data_ptr(), _stream()))
+    return sink
 
 
 def selftest_bounds(device="cuda"):

@@ -315,3 +315,13 @@ def test_long_sequences_many_drafts_and_big_trees(race, oracle_mod):
     run_case(race, oracle_mod, wl.shrink(wl.WORKLOADS[3], B=2, m=300, k=3, V=40), note="m = 300")
     run_case(race, oracle_mod, wl.shrink(wl.WORKLOADS[4], B=2, N=5000, V=16), note="N = 5000")
     run_case(race, oracle_mod, wl.shrink(wl.WORKLOADS[1], B=3000, k=1, V=8), note="B = 3000")
+
+
+def test_read_probe_runs_and_leaves_its_inputs_alone(race):
+    x = torch.randn(3, 5, 4096, device="cuda")
+    y = torch.randn(7, 4096, device="cuda").to(torch.bfloat16)
+    x0, y0 = x.clone(), y.clone()
+    sink = race.read_probe(x, y)
+    race.read_probe(y)
+    torch.cuda.synchronize()
+    assert torch.equal(x, x0) and torch.equal(y, y0) and int(sink.item()) in (0, 1)
