@@ -144,6 +144,7 @@ struct Seg {
 
 struct Lds {
     float tau[2];        // the workgroup's lower bound of the row maximum, per side (raised with LDS float max)
+    float tau_u[2];      // the same with its margin, in the filter's units: what the stream compares against
     int32_t count[2];    // candidates appended (may exceed kListCap: overflow)
     int32_t idx[2][kListCap];
     uint32_t word[2][kListCap];
@@ -233,14 +234,16 @@ __device__ __forceinline__ Raw load_raw(const char* row, int32_t ia, int32_t ib,
     // segment's last piece instead, and the refine step never accepts a token index >= end.  A row starts wherever
     // the vocabulary size puts it, so the loads promise no more than element alignment (the hardware serves
     // unaligned 128-bit global loads; aligned rows lose nothing).
+    // Byte offsets within a row fit 32 bits (the vocabulary is at most 2^30 tokens), so a load is the row's
+    // address, which is the same for the whole wavefront, plus a 32-bit offset per lane: no 64-bit address arithmetic.
     typedef u32x4 u32x4_unaligned __attribute__((aligned(2)));
-    constexpr int es = DT == ERSD_BF16 ? 2 : 4;
+    constexpr uint32_t es = DT == ERSD_BF16 ? 2 : 4;
     const int32_t last = end - TileShape<DT>::kTokPerPiece;
-    const int32_t ca = ia < last ? ia : last;
-    const int32_t cb = ib < last ? ib : last;
+    const uint32_t oa = (uint32_t)(ia < last ? ia : last) * es;
+    const uint32_t ob = (uint32_t)(ib < last ? ib : last) * es;
     Raw r;
-    r.a = __builtin_nontemporal_load(reinterpret_cast<const u32x4_unaligned*>(row + (size_t)ca * es));
-    r.b = __builtin_nontemporal_load(reinterpret_cast<const u32x4_unaligned*>(row + (size_t)cb * es));
+    r.a = __builtin_nontemporal_load(reinterpret_cast<const u32x4_unaligned*>(row + oa));
+    r.b = __builtin_nontemporal_load(reinterpret_cast<const u32x4_unaligned*>(row + ob));
     return r;
 }
 
@@ -249,12 +252,14 @@ __device__ __forceinline__ Raw load_raw(const char* row, int32_t ia, int32_t ib,
 struct HotConsts {
     float c2s;       // 2^23 * log2(e) / T: the logit's factor in the filter's fixed-point units (see bound_units)
     uint32_t sh16;   // the shift count 16
+    uint32_t himask; // the upper half of a word: the odd element of a bf16 pair
 };
 __device__ __forceinline__ HotConsts make_hot_consts(float c2) {
     HotConsts h;
     const float c2s = c2 * 0x1p23f;
     asm volatile("v_mov_b32 %0, %1" : "=v"(h.c2s) : "s"(c2s));
     asm volatile("v_mov_b32 %0, 16" : "=v"(h.sh16));
+    asm volatile("v_mov_b32 %0, 0xffff0000" : "=v"(h.himask));
     return h;
 }
 
@@ -321,8 +326,15 @@ __device__ __forceinline__ float wave_max(float v) {
 __device__ __forceinline__ float lds_tau(const Lds& lds, int side) {
     return __hip_atomic_load(&lds.tau[side], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
+// The threshold the stream compares a bound against.  Every value ever stored comes from a valid lower bound of the
+// row maximum, so the largest of them is valid too.
+__device__ __forceinline__ float lds_tau_units(const Lds& lds, int side) {
+    return __hip_atomic_load(&lds.tau_u[side], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
 __device__ __forceinline__ void lds_tau_raise(Lds& lds, int side, float v) {
     __hip_atomic_fetch_max(&lds.tau[side], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    __hip_atomic_fetch_max(&lds.tau_u[side], tau_units(with_margin(v)), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
 // Arrival trees, draft side: tau must stay below the nq-th largest score of the segment.  lds.top holds lower
@@ -404,9 +416,9 @@ __device__ __forceinline__ float raw_logit_const(const Raw& r, int e) {
 template <bool RAWF32, bool HASQ>
 __device__ __forceinline__ void refine_tile(Lds& lds, float c2, int32_t i0, int32_t i1, int32_t end, const Raw& rq,
                                             const Raw& rp, const uint32_t (&x)[8], const float (&up)[8],
-                                            const float (&uq)[8], bool flag, float tauq_u, float taup_u, float& tauq,
-                                            float& taup, int32_t nq) {
+                                            const float (&uq)[8], bool flag, float tauq_u, float taup_u, int32_t nq) {
     if (!flag) return;
+    float taup = lds_tau(lds, 1), tauq = HASQ ? lds_tau(lds, 0) : kTauInit;
     // which of this lane's (token, side) bounds reach tau: bits 0-7 target side, 8-15 draft side
     uint32_t mask = 0;
 #pragma unroll
@@ -436,60 +448,101 @@ __device__ __forceinline__ void refine_tile(Lds& lds, float c2, int32_t i0, int3
     if (HASQ && tauq > tauq0) lds_tau_raise(lds, 0, tauq);
 }
 
+// The largest of the 8 logits a lane holds for one row of a tile, without widening them one by one.
+//   fp32: a tree of three-input maxima.
+//   bf16: the ordering of finite values of any IEEE-style format is the ordering of their sign-magnitude bit
+//         patterns, so the packed half-precision maximum orders bf16 pairs correctly as long as no pattern reads
+//         as a half-precision NaN (top five exponent bits set: |value| >= 2^121, infinities, NaN).  A -inf logit
+//         (a masked token) reads as a quiet NaN, which the instruction drops in favour of the other operand, and
+//         if all four operands of one half are masked the result is either -inf again or a NaN pattern that reads
+//         as a huge bf16, which only sends the lane to the per-token bounds below.  The library's self-test checks
+//         the instruction against the fp32 comparison for every pair of in-domain bf16 patterns.
+// The instructions are written out because the compiler would first quiet possible signalling NaNs of loaded
+// values, one more instruction per operand.
+template <bool RAWF32>
+__device__ __forceinline__ float group_max(const Raw& r, uint32_t himask, uint32_t sh16) {
+    float m;
+    if (RAWF32) {
+        float m0, m1, m2;
+        asm("v_max3_f32 %0, %1, %2, %3" : "=v"(m0) : "v"(r.a.x), "v"(r.a.y), "v"(r.a.z));
+        asm("v_max3_f32 %0, %1, %2, %3" : "=v"(m1) : "v"(r.a.w), "v"(r.b.x), "v"(r.b.y));
+        asm("v_max3_f32 %0, %1, %2, %3" : "=v"(m2) : "v"(r.b.z), "v"(r.b.w), "v"(m0));
+        asm("v_max_f32 %0, %1, %2" : "=v"(m) : "v"(m1), "v"(m2));
+    } else {
+        uint32_t m01, m23, m4;
+        asm("v_pk_max_f16 %0, %1, %2" : "=v"(m01) : "v"(r.a.x), "v"(r.a.y));
+        asm("v_pk_max_f16 %0, %1, %2" : "=v"(m23) : "v"(r.a.z), "v"(r.a.w));
+        asm("v_pk_max_f16 %0, %1, %2" : "=v"(m4) : "v"(m01), "v"(m23));
+        const uint32_t hi = m4 & himask, lo = m4 << sh16;
+        asm("v_max_f32 %0, %1, %2" : "=v"(m) : "v"(hi), "v"(lo));
+    }
+    return m;
+}
+
 // The per-iteration work of one lane: 8 tokens of one or two rows.
 template <bool RAWF32, bool HASQ, bool ARR>
 __device__ __forceinline__ void filter_tile(const RaceArgs& a, const Seg& c, Lds& lds, const HotConsts& h, int32_t i0,
-                                            int32_t i1, const Raw& rq, const Raw& rp, float& tauq, float& taup) {
-    // tau with its margin, in the filter's units.  The comparisons are strict, so a bound of -inf (a masked token)
-    // never passes, not even while tau is still at its start value (which these units turn into -inf).
+                                            int32_t i1, const Raw& rq, const Raw& rp, float tauq_u, float taup_u) {
+    // tauq_u / taup_u: tau with its margin, in the filter's units.  The comparisons are strict, so a bound of -inf
+    // (a masked token) never passes, not even while tau is still at its start value (-inf in these units).
     const float c2s = h.c2s;
-    const float taup_u = tau_units(with_margin(taup));
-    const float tauq_u = HASQ ? tau_units(with_margin(tauq)) : 0.0f;
 
     uint32_t x[8];
     philox4x32((uint32_t)i0 >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, x);      // tokens i0 .. i0 + 3
     philox4x32((uint32_t)i1 >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, x + 4);  // tokens i1 .. i1 + 3
-    float lp[8], lq[8];
-    unpack<RAWF32>(rp, lp, h.sh16);
-    if (HASQ) unpack<RAWF32>(rq, lq, h.sh16);
 
-    float accp = -INFINITY, accq = -INFINITY;
-    float up[8], uq[8];  // per-token upper bounds of the two scores, in the filter's units
+    // One bound for the whole group first: the largest logit with the smallest word.  The word's term is
+    // non-increasing in the word and the logit's factor is positive, and conversions and the fused multiply-add
+    // round monotonically, so this is at least every token's own bound: if it stays below tau, so do all eight.
+    const uint32_t xmin = min(min(min(x[0], x[1]), min(x[2], x[3])), min(min(x[4], x[5]), min(x[6], x[7])));
+    const float tmin = bound_units(xmin);
+    // (the two tests are combined without a short cut: a branch would cost more than the second bound)
+    const bool gp = fmaf(group_max<RAWF32>(rp, h.himask, h.sh16), c2s, -tmin) > taup_u;
+    const bool gq = HASQ ? fmaf(group_max<RAWF32>(rq, h.himask, h.sh16), c2s, -tmin) > tauq_u : false;
+    const bool gflag = gp | gq;
+
+    if (__builtin_amdgcn_ballot_w64(gflag) != 0) {  // some lane holds a group that may matter: token by token
+        float lp[8], lq[8];
+        unpack<RAWF32>(rp, lp, h.sh16);
+        if (HASQ) unpack<RAWF32>(rq, lq, h.sh16);
+        float accp = -INFINITY, accq = -INFINITY;
+        float up[8], uq[8];  // per-token upper bounds of the two scores, in the filter's units
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const float t = bound_units(x[e]);
-        up[e] = fmaf(lp[e], c2s, -t);
-        accp = fmaxf(accp, up[e]);
-        if (HASQ) {
-            uq[e] = fmaf(lq[e], c2s, -t);
-            accq = fmaxf(accq, uq[e]);
+        for (int e = 0; e < 8; ++e) {
+            const float t = bound_units(x[e]);
+            up[e] = fmaf(lp[e], c2s, -t);
+            accp = fmaxf(accp, up[e]);
+            if (HASQ) {
+                uq[e] = fmaf(lq[e], c2s, -t);
+                accq = fmaxf(accq, uq[e]);
+            }
         }
+        bool flag = accp > taup_u;
+        if (HASQ) flag = flag || (accq > tauq_u);
+        if (__builtin_amdgcn_ballot_w64(flag) != 0)  // rarer still: some token's own bound reaches tau
+            refine_tile<RAWF32, HASQ>(lds, a.c2, i0, i1, c.end, rq, rp, x, up, uq, flag, tauq_u, taup_u,
+                                      ARR ? c.nq : 0);
     }
-    bool flag = accp > taup_u;
-    if (HASQ) flag = flag || (accq > tauq_u);
-
-    if (__builtin_amdgcn_ballot_w64(flag) != 0)  // rare: some lane holds a token that may matter
-        refine_tile<RAWF32, HASQ>(lds, a.c2, i0, i1, c.end, rq, rp, x, up, uq, flag, tauq_u, taup_u, tauq, taup,
-                                  ARR ? c.nq : 0);
 }
 
 // One lane's share of a tile: its two pieces.  A bf16 piece is 8 tokens and is filtered on its own; two fp32
 // pieces make one group of 8.
 template <int DT, bool HASQ, bool ARR>
 __device__ __forceinline__ void filter_lane(const RaceArgs& a, const Seg& c, Lds& lds, const HotConsts& h, int32_t ia,
-                                            int32_t ib, const Raw& rq, const Raw& rp, float& tauq, float& taup) {
+                                            int32_t ib, const Raw& rq, const Raw& rp) {
     constexpr bool RAWF32 = DT == ERSD_F32;
-    // the workgroup's bound, possibly raised by another wavefront since the last tile
-    taup = fmaxf(taup, lds_tau(lds, 1));
-    if (HASQ) tauq = fmaxf(tauq, lds_tau(lds, 0));
+    // The workgroup's thresholds as they stand now: every lane publishes what it learns (refine_tile), so the
+    // value in LDS is at least this lane's own and nothing is kept in registers from tile to tile.
+    const float taup_u = lds_tau_units(lds, 1);
+    const float tauq_u = HASQ ? lds_tau_units(lds, 0) : 0.0f;
     if (DT == ERSD_BF16) {
         Raw hq, hp;
         hq.a = rq.a; hq.b = rq.a; hp.a = rp.a; hp.b = rp.a;
-        filter_tile<RAWF32, HASQ, ARR>(a, c, lds, h, ia, ia + 4, hq, hp, tauq, taup);
+        filter_tile<RAWF32, HASQ, ARR>(a, c, lds, h, ia, ia + 4, hq, hp, tauq_u, taup_u);
         hq.a = rq.b; hq.b = rq.b; hp.a = rp.b; hp.b = rp.b;
-        filter_tile<RAWF32, HASQ, ARR>(a, c, lds, h, ib, ib + 4, hq, hp, tauq, taup);
+        filter_tile<RAWF32, HASQ, ARR>(a, c, lds, h, ib, ib + 4, hq, hp, tauq_u, taup_u);
     } else {
-        filter_tile<RAWF32, HASQ, ARR>(a, c, lds, h, ia, ib, rq, rp, tauq, taup);
+        filter_tile<RAWF32, HASQ, ARR>(a, c, lds, h, ia, ib, rq, rp, tauq_u, taup_u);
     }
 }
 
@@ -506,9 +559,9 @@ __device__ __forceinline__ float wave_nth_largest(float v0, float v1, int32_t n)
     return m;
 }
 
-// The stream over a token range whose end is a multiple of 8.  tauq / taup return the lane's bounds.
+// The stream over a token range whose end is a multiple of 8.
 template <int DT, bool HASQ, bool ARR>
-__device__ void filter_stream(const RaceArgs& a, const Seg& c, Lds& lds, float& tauq, float& taup) {
+__device__ void filter_stream(const RaceArgs& a, const Seg& c, Lds& lds) {
     constexpr bool RAWF32 = DT == ERSD_F32;
     typedef TileShape<DT> TS;
     constexpr int kTile = TS::kTile;
@@ -534,6 +587,7 @@ __device__ void filter_stream(const RaceArgs& a, const Seg& c, Lds& lds, float& 
     {
         uint32_t w[4];
         philox4x32((uint32_t)first >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, w);
+        float taup = kTauInit, tauq = kTauInit;
         float bq[2] = {kTauInit, kTauInit};
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
@@ -586,8 +640,7 @@ __device__ void filter_stream(const RaceArgs& a, const Seg& c, Lds& lds, float& 
                 const int32_t nt = base + (st + kAhead) * kTile, ct = base + st * kTile;
                 pr[nb] = load_raw<DT>(c.prow, TS::piece_a(nt, tid), TS::piece_b(nt, tid), c.end);
                 if (HASQ) q[nb] = load_raw<DT>(c.qrow, TS::piece_a(nt, tid), TS::piece_b(nt, tid), c.end);
-                filter_lane<DT, HASQ, ARR>(a, c, lds, h, TS::piece_a(ct, tid), TS::piece_b(ct, tid), q[st], pr[st],
-                                           tauq, taup);
+                filter_lane<DT, HASQ, ARR>(a, c, lds, h, TS::piece_a(ct, tid), TS::piece_b(ct, tid), q[st], pr[st]);
                 done = base + (st + 1) * kTile >= c.end;  // workgroup-uniform
             }
         }
@@ -601,15 +654,15 @@ __device__ void filter_stream(const RaceArgs& a, const Seg& c, Lds& lds, float& 
 // vocabulary size that is not a multiple of 8), which go straight to the refine step.
 template <int DT, bool HASQ, bool ARR>
 __device__ void filter_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
-    float tauq = kTauInit, taup = kTauInit;
     const int32_t vend = c.end & ~7;  // c.begin is a multiple of 8
     if (vend > c.begin) {
         Seg v = c;
         v.end = vend;
-        filter_stream<DT, HASQ, ARR>(a, v, lds, tauq, taup);
+        filter_stream<DT, HASQ, ARR>(a, v, lds);
     }
     const int32_t i = vend + (int32_t)threadIdx.x;
     if (i < c.end) {  // at most seven lanes
+        float taup = lds_tau(lds, 1), tauq = HASQ ? lds_tau(lds, 0) : kTauInit;
         uint32_t w[4];
         philox4x32((uint32_t)i >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, w);
         const uint32_t x = pick4(u32x4{w[0], w[1], w[2], w[3]}, i & 3);
@@ -624,6 +677,15 @@ __device__ void filter_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
     }
 }
 
+// Barrier of a workgroup that orders its LDS traffic only.  __syncthreads() also waits for every global store the
+// wavefront has issued to be acknowledged, which under a streaming load takes microseconds; the survivor records a
+// segment writes are read by the finishing kernel, never by this one, so the race kernels need no such wait.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // fp32 score of a (logit, word) record, exactly as the refine step computes it
 __device__ __forceinline__ float score2(float logit, uint32_t word, float c2) {
     return fmaf(logit, c2, -log2_exponential(word));
@@ -635,15 +697,16 @@ __device__ void race_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
     const int tid = threadIdx.x;
     if (tid < 2) {
         lds.tau[tid] = kTauInit;
+        lds.tau_u[tid] = -INFINITY;
         lds.count[tid] = 0;
         lds.nsurv[tid] = 0;
     }
-    __syncthreads();
+    lds_barrier();
     if (!a.exhaustive) {
         if (c.qrow) filter_segment<DT, true, false>(a, c, lds);
         else filter_segment<DT, false, false>(a, c, lds);
     }
-    __syncthreads();
+    lds_barrier();
 
     // Wavefronts 0-1 take the draft side, 2-3 the target side.
     const int side = tid / (kThreads / 2);
@@ -661,7 +724,7 @@ __device__ void race_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
             }
         }
     }
-    __syncthreads();
+    lds_barrier();
     SegOut* out = row ? a.out + (c.row * 2 + side) * a.part.nslot + c.slot : nullptr;
     const int32_t ns = lds.nsurv[side];
     const bool common = listed && ns <= kMaxSurvivors;
@@ -693,7 +756,7 @@ __device__ void race_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
         wave_argmax(bs, bi);
         if ((tid & (kWave - 1)) == 0) { lds.red_s[tid / kWave] = bs; lds.red_i[tid / kWave] = bi; }
     }
-    __syncthreads();
+    lds_barrier();
     if (!common && row && half_tid == 0) {
         const int w0 = side * (kWaves / 2);
         bs = lds.red_s[w0];
@@ -783,17 +846,18 @@ __device__ void race_segment_arr(const RaceArgs& a, const Seg& c, Lds& lds) {
     const int tid = threadIdx.x;
     if (tid < 2) {
         lds.tau[tid] = kTauInit;
+        lds.tau_u[tid] = -INFINITY;
         lds.count[tid] = 0;
         lds.nsurv[tid] = 0;
     }
     if (tid < kMaxRank) lds.top[tid] = kTauInit;
     if (tid == 0) lds.rounds = 0;
-    __syncthreads();
+    lds_barrier();
     if (!a.exhaustive) {
         if (c.qrow) filter_segment<DT, true, true>(a, c, lds);
         else filter_segment<DT, false, true>(a, c, lds);
     }
-    __syncthreads();
+    lds_barrier();
 
     // Wavefronts 0-1 take the draft side, 2-3 the target side.
     const int side = tid / (kThreads / 2);
@@ -812,7 +876,7 @@ __device__ void race_segment_arr(const RaceArgs& a, const Seg& c, Lds& lds) {
             }
         }
     }
-    __syncthreads();
+    lds_barrier();
     int32_t* out_count = nullptr;
     Cand* out_rec = nullptr;
     if (row) {
@@ -844,7 +908,7 @@ __device__ void race_segment_arr(const RaceArgs& a, const Seg& c, Lds& lds) {
             out_rec[half_tid] = k;
         }
     }
-    __syncthreads();
+    lds_barrier();
     const int32_t rounds = lds.rounds;  // workgroup-uniform
     const bool from_list = !(a.exhaustive || n > kListCap);
     double ps = 0.0;
@@ -868,7 +932,7 @@ __device__ void race_segment_arr(const RaceArgs& a, const Seg& c, Lds& lds) {
             wave_argmax(bs, bi);
             if ((tid & (kWave - 1)) == 0) { lds.red_s[tid / kWave] = bs; lds.red_i[tid / kWave] = bi; }
         }
-        __syncthreads();
+        lds_barrier();
         if (mine) {  // every thread of the half combines its side's wavefronts the same way
             const int w0 = side * (kWaves / 2);
             bs = lds.red_s[w0];
@@ -896,7 +960,7 @@ __device__ void race_segment_arr(const RaceArgs& a, const Seg& c, Lds& lds) {
                 ++picked;
             }
         }
-        __syncthreads();
+        lds_barrier();
     }
     if (my_rounds > 0 && half_tid == 0) *out_count = picked;
 }
@@ -1424,7 +1488,7 @@ int env_int(const char* name, int dflt) {
 
 bool sizes_ok(int32_t B, int32_t m, int32_t kd, int32_t kt, int32_t V) {
     if (B < 1 || m < 1 || kd < 1 || kt < 1 || V < 1) return false;
-    if (V > 0x7fff0000) return false;                         // token indices stay in int32
+    if (V > (1 << 30)) return false;                          // token indices in int32, byte offsets within a row in 32 bits
     const int64_t rows = (int64_t)B * m * kt;
     if (rows > 0x7fffffff) return false;                      // grids and row indices
     const int64_t v8 = ((int64_t)V + 7) / 8;
