@@ -36,13 +36,14 @@
  *
  * Layout: tensors are row-major and contiguous with the vocabulary axis innermost; the draft and the
  * target tensor have the same element type.  Logit pointers must be 16-byte aligned, int32 outputs
- * 4-byte aligned, the workspace 16-byte aligned.  V may be any positive value: rows are streamed with
+ * 4-byte aligned, the workspace 16-byte aligned.  V may be any value from 1 to 2^30: rows are streamed with
  * 128-bit loads whatever their alignment (a V that is not a multiple of 8 costs a few percent).
  *
  * Logit contents: -inf is a legal masked token and never wins unless its whole row is -inf, in which
- * case token 0 wins.  Finite logits must satisfy |logit| / T < 2^100 (the streaming filter works in
- * fp32; beyond that its products overflow).  NaN and +inf logits, and finite ones beyond that limit,
- * give unspecified tokens (never a fault).
+ * case token 0 wins.  Finite logits must satisfy |logit| < 2^100 and |logit| / T < 2^100 (the streaming
+ * filter works in fp32, beyond that its products overflow, and it orders bf16 logits by their bit patterns,
+ * which holds below 2^121).  NaN and +inf logits, and finite ones beyond those limits, give unspecified
+ * tokens (never a fault).
  *
  * Errors: every argument error is detected on the host before any HIP call is made and is returned
  * as a negative status; nothing is enqueued in that case.  ERSD_ERR_HIP reports a failed launch.
@@ -155,16 +156,32 @@ int ersd_race_stage_accept(int variant, ersd_dtype dt, int32_t B, int32_t m, int
                            const void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Host-only description of how a job is cut into equal shares for `blocks` workgroups (1..4096): every
+ * Host-only description of how a job is cut into shares of equal cost for `blocks` workgroups (1..4096): every
  * row is a run of 8-token groups, rows are laid end to end, and share b covers the global group indices
- * [block_start[b], block_start[b+1]).  A row's partial winners are written by the workgroups
- * row_first[r] .. row_last[r], one slot each, at most *out_nslot of them.
- *   out_G, out_nslot: never NULL.  block_start: NULL or [G + 1] (G <= blocks).  row_first, row_last: both
- *   NULL or both [rows], rows = B * m * (k + 1) or B * N.  All HOST arrays.  No device work is done.
+ * [block_start[b], block_start[b+1]).  The cost of a share is 10 per group of a row pair, 5 per group of a
+ * target-only row, plus *out_seg_cost for every row whose first group it holds.  A row's partial winners are
+ * written by the workgroups row_first[r] .. row_last[r], one slot each, at most *out_nslot of them.
+ *   out_G, out_nslot: never NULL.  out_seg_cost: may be NULL.  block_start: NULL or [G + 1] (G <= blocks).
+ *   row_first, row_last: both NULL or both [rows], rows = B * m * (k + 1) or B * N.  All HOST arrays.  No device
+ *   work is done.
  */
-int ersd_plan_describe_host(int variant, int32_t B, int32_t m, int32_t k_or_N, int32_t V, uint32_t blocks,
-                            uint32_t* out_G, uint32_t* out_nslot, uint64_t* block_start,
-                            uint32_t* row_first, uint32_t* row_last);
+int ersd_plan_describe_host(int variant, int32_t B, int32_t m, int32_t k_or_N, int32_t V, ersd_dtype dt,
+                            uint32_t blocks, uint32_t* out_G, uint32_t* out_nslot, uint32_t* out_seg_cost,
+                            uint64_t* block_start, uint32_t* row_first, uint32_t* row_last);
+
+/*
+ * Test and tuning hooks: not part of the product interface.  Process-wide settings that the tests use to reach
+ * code paths a default launch does not take (a row cut into many segments, the exhaustive scoring path).  A
+ * field at its default leaves the library's own choice in place; NULL restores all defaults.
+ * Set them while no call of this library is running, and keep them unchanged between the two stage calls of one
+ * job and between a workspace-size query and the call it serves.
+ */
+typedef struct {
+    int32_t force_blocks;      /* > 0: workgroups the race kernels are launched with (default 0: as many as are resident) */
+    int32_t exhaustive;        /* != 0: every token is scored in double precision inside the race kernels (default 0) */
+    int32_t seg_cost_units;    /* >= 0: cost charged to every row start when the job is cut up (default -1) */
+} ersd_test_hooks;
+void ersd_test_hooks_set(const ersd_test_hooks* hooks);
 
 /*
  * The race of ONE model's logits, for callers that draft and verify at different times (the order of
@@ -316,11 +333,13 @@ size_t ersd_gsd_workspace_bytes(int32_t B, int32_t k, int32_t V, ersd_dtype dt);
 int ersd_max_rank(void);
 
 /*
- * Device self-check of the two single-precision bounds the streaming filter relies on, over all 2^32
- * generator words, against double precision.  counters: DEVICE array of 4 uint64, written as
+ * Device self-check of the facts the streaming filter relies on.  The two single-precision bounds, over all 2^32
+ * generator words, against double precision; and the packed half-precision maximum used as an order on bf16 bit
+ * patterns, over all pairs of in-domain patterns.  counters: DEVICE array of 5 uint64, written as
  *   [0] words whose cheap upper bound of -log2 e fell below the true value      (must be 0)
  *   [1] words whose refined log2 e is off by more than 2^-9                    (must be 0)
  *   [2] largest refinement error, [3] largest upper-bound slack (IEEE fp32 bit patterns)
+ *   [4] bf16 pairs whose packed maximum fell below the larger value             (must be 0)
  * Enqueues on `stream`; takes a fraction of a second.
  */
 int ersd_selftest_bounds(uint64_t* counters, void* stream);

@@ -1,7 +1,9 @@
 // How the rows of one call are shared out: all rows are laid end to end in 8-token groups, weighted by what a group
-// costs, and cut into G equal shares, one per workgroup.  Host and device evaluate the same functions, so the race
-// kernel (which part is mine, which slot do I write), the finishing kernels (which slots does a row have) and the
-// host (workspace size, ersd_plan_describe_host) agree by construction.
+// costs, with a fixed charge in front of every row (a workgroup that starts a second row pays for an empty load
+// pipeline, a new bound and a hand-over: several microseconds), and cut into G equal shares, one per workgroup.
+// Host and device evaluate the same functions, so the race kernel (which part is mine, which slot do I write),
+// the finishing kernels (which slots does a row have) and the host (workspace size, ersd_plan_describe_host)
+// agree by construction.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -11,9 +13,12 @@ namespace ersd_part {
 
 #ifndef ERSD_W_PAIR
 #define ERSD_W_PAIR 10
-#define ERSD_W_SINGLE 7
+#define ERSD_W_SINGLE 5
 #endif
-constexpr uint32_t kWPair = ERSD_W_PAIR, kWSingle = ERSD_W_SINGLE;  // relative cost of one group in a pair row / target-only row
+// Relative cost of one group in a pair row / target-only row: what it costs to read them.  (While the filter was
+// bound by its arithmetic a target-only group, with a generator word per logit, cost 0.7 of a pair group; now a
+// share made of target-only rows alone runs in 0.45 to 0.5 of the time of a share of pair rows with as many groups.)
+constexpr uint32_t kWPair = ERSD_W_PAIR, kWSingle = ERSD_W_SINGLE;
 constexpr uint64_t kMinQuota = 64 * kWPair * 16;     // cost units a workgroup gets at least (16 pair iterations of a wave)
 
 // Balanced partition of the concatenated rows (in 8-token groups) over G workgroups.  Shared by the race
@@ -22,6 +27,8 @@ struct Part {
     uint64_t U;           // total cost units
     uint64_t Us;          // cost units per sequence
     uint64_t pair_units;  // cost units of the pair rows of one sequence
+    uint32_t S;           // cost units charged to every row start (0 with a weight table)
+    uint32_t Lp, Ls;      // cost units of a whole pair row / target-only row: S + weight * V8
     uint64_t rows;        // target rows = races
     uint32_t V8;          // groups per row
     uint32_t kd, kt;      // draft rows / target rows per sequence
@@ -32,7 +39,7 @@ struct Part {
     // multiplication with reciprocals prepared on the host (see magic_of); otherwise by plain 64-bit division.
     uint32_t fast;
     uint32_t q, r;        // U / G and U % G: share b starts at unit b * q + (b * r) / G = floor(b * U / G)
-    uint64_t m_G, m_q, m_Us, m_pair_row, m_single_row, m_kt;  // reciprocals of G, q, Us, kWPair*V8, kWSingle*V8, kt
+    uint64_t m_G, m_q, m_Us, m_pair_row, m_single_row, m_kt;  // reciprocals of G, q, Us, Lp, Ls, kt
     // Arrival trees: which contexts have a draft row is known on the device only.  wprefix[c] = summed weights of
     // the contexts before c (kt + 1 entries, device memory); nullptr for the closed-form layouts above.
     const uint32_t* wprefix;
@@ -79,13 +86,16 @@ __host__ __device__ inline PartPos part_unit_to_pos(const Part& p, uint64_t u) {
     if (p.fast) {  // closed-form layout, everything below 2^32
         const uint32_t u32 = (uint32_t)u, seq = magic_div(u32, p.m_Us), rem = u32 - seq * (uint32_t)p.Us;
         o.seq = seq;
+        // (a unit inside a row's start charge stands for the row's first group)
         if (rem < (uint32_t)p.pair_units) {
             o.j = magic_div(rem, p.m_pair_row);
-            o.grp = (rem - o.j * (kWPair * p.V8)) / kWPair;
+            const uint32_t off = rem - o.j * p.Lp;
+            o.grp = off < p.S ? 0 : (off - p.S) / kWPair;
         } else {
             const uint32_t r2 = rem - (uint32_t)p.pair_units, jj = magic_div(r2, p.m_single_row);
             o.j = p.kd + jj;
-            o.grp = (r2 - jj * (kWSingle * p.V8)) / kWSingle;
+            const uint32_t off = r2 - jj * p.Ls;
+            o.grp = off < p.S ? 0 : (off - p.S) / kWSingle;
         }
         o.row = (uint64_t)seq * p.kt + o.j;
         return o;
@@ -96,12 +106,13 @@ __host__ __device__ inline PartPos part_unit_to_pos(const Part& p, uint64_t u) {
         row = part_table_row(p, rem / p.V8);
         grp = (rem - (uint64_t)p.wprefix[row] * p.V8) / (p.wprefix[row + 1] - p.wprefix[row]);
     } else if (rem < p.pair_units) {
-        row = rem / ((uint64_t)kWPair * p.V8);
-        grp = (rem % ((uint64_t)kWPair * p.V8)) / kWPair;
+        row = rem / p.Lp;
+        const uint64_t off = rem % p.Lp;
+        grp = off < p.S ? 0 : (off - p.S) / kWPair;
     } else {
-        const uint64_t r2 = rem - p.pair_units;
-        row = p.kd + r2 / ((uint64_t)kWSingle * p.V8);
-        grp = (r2 % ((uint64_t)kWSingle * p.V8)) / kWSingle;
+        const uint64_t r2 = rem - p.pair_units, off = r2 % p.Ls;
+        row = p.kd + r2 / p.Ls;
+        grp = off < p.S ? 0 : (off - p.S) / kWSingle;
     }
     o.seq = seq;
     o.j = (uint32_t)row;
@@ -118,14 +129,14 @@ __host__ __device__ inline uint64_t part_block_start_unit(const Part& p, uint32_
 __host__ __device__ inline PartPos part_start_pos(const Part& p, uint32_t b) {
     return part_unit_to_pos(p, part_block_start_unit(p, b));
 }
-// first cost unit and weight of row (seq, j)
+// first cost unit of the groups of row (seq, j), after the row's start charge, and the weight of a group
 __host__ __device__ inline uint64_t part_row_unit(const Part& p, uint64_t seq, uint32_t j, uint32_t* w) {
     if (p.wprefix) {
         *w = p.wprefix[j + 1] - p.wprefix[j];
         return seq * p.Us + (uint64_t)p.wprefix[j] * p.V8;
     }
     *w = j < p.kd ? kWPair : kWSingle;
-    return seq * p.Us + (j < p.kd ? (uint64_t)j * kWPair * p.V8 : p.pair_units + (uint64_t)(j - p.kd) * kWSingle * p.V8);
+    return seq * p.Us + p.S + (j < p.kd ? (uint64_t)j * p.Lp : p.pair_units + (uint64_t)(j - p.kd) * p.Ls);
 }
 // workgroup whose share contains cost unit x < U: the largest b with floor(b * U / G) <= x
 __host__ __device__ inline uint32_t part_block_of_unit(const Part& p, uint64_t x) {

@@ -33,7 +33,6 @@
 #include <atomic>
 #include <cmath>
 #include <cstdint>
-#include <cstdlib>
 #include <cstring>
 
 #include "ersd.h"
@@ -786,12 +785,24 @@ __device__ void race_segment(const RaceArgs& a, const Seg& c, Lds& lds) {
 #define ERSD_WAVES_PER_EU 3
 #endif
 
+// Which share a workgroup takes.  The hardware deals workgroups out to the eight accelerator dies (XCDs) in turn,
+// workgroup i to die i mod 8, while the kind of a share (how many row starts it holds, whether it lies in
+// target-only rows) repeats with the rows of a sequence; share = workgroup index would hand a die the same few
+// kinds of share over and over, and the dies with the heavier kinds finish microseconds after the others.  Die x
+// takes a contiguous range of shares instead, which holds every kind in the proportion of the whole job.
+__device__ __forceinline__ uint32_t xcd_share(uint32_t block, uint32_t G) {
+    constexpr uint32_t kXcds = 8;
+    const uint32_t x = block % kXcds, per = G / kXcds, extra = G % kXcds;
+    return x * per + (x < extra ? x : extra) + block / kXcds;
+}
+
 template <int DT>
 __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ERSD_WAVES_PER_EU, 8)))
 race_kernel(RaceArgs a) {
     __shared__ Lds lds;
     const Part& p = a.part;
-    const PartPos first = part_start_pos(p, blockIdx.x), last = part_start_pos(p, blockIdx.x + 1);
+    const uint32_t share = xcd_share(blockIdx.x, p.G);
+    const PartPos first = part_start_pos(p, share), last = part_start_pos(p, share + 1);
     const size_t es = DT == ERSD_F32 ? 4 : 2;
     // (row, sequence, position, prompt, draft) of the first segment; later segments start at the next row's
     // first group, so they follow by counting up
@@ -815,7 +826,7 @@ race_kernel(RaceArgs a) {
         const int64_t e = (int64_t)g1 * 8;
         c.end = e < a.V ? (int32_t)e : a.V;
         // a segment that starts at its row's first group is that row's first writer
-        c.slot = g0 == 0 ? 0 : blockIdx.x - part_first_block(p, seq, j);
+        c.slot = g0 == 0 ? 0 : share - part_first_block(p, seq, j);
         race_segment<DT>(a, c, lds);
         g0 = 0;
         ++row;
@@ -1436,6 +1447,24 @@ __global__ void __launch_bounds__(kThreads) selftest_bounds_kernel(unsigned long
         if (!(err <= 0x1p-9f)) ++bad_refine;
         max_err = fmaxf(max_err, err);
     }
+    // The packed half-precision maximum as an order on bf16 bit patterns (group_max): every pair of patterns, one in
+    // each half of a word, both either finite with |value| < 2^121 or -inf.  The result must not be below the larger
+    // of the two values (it may be above it only in the all-masked case, where the per-token bounds take over).
+    unsigned long long bad_pkmax = 0;
+    for (uint64_t xi = (uint64_t)blockIdx.x * kThreads + threadIdx.x; xi < (1ull << 32); xi += stride) {
+        const uint32_t pa = (uint32_t)xi >> 16, pb = (uint32_t)xi & 0xffffu;
+        const bool in_a = ((pa >> 10) & 0x1f) != 0x1f || pa == 0xff80u, in_b = ((pb >> 10) & 0x1f) != 0x1f || pb == 0xff80u;
+        if (!in_a || !in_b) continue;
+        uint32_t m;
+        asm volatile("v_pk_max_f16 %0, %1, %2" : "=v"(m) : "v"(pa), "v"(pb));   // low halves compared
+        const float fa = __uint_as_float(pa << 16), fb = __uint_as_float(pb << 16);
+        const float got = __uint_as_float(m << 16);
+        if (!(got >= fmaxf(fa, fb))) ++bad_pkmax;
+        uint32_t mh;
+        asm volatile("v_pk_max_f16 %0, %1, %2" : "=v"(mh) : "v"(pa << 16), "v"(pb << 16));   // high halves compared
+        if ((mh >> 16) != (m & 0xffffu)) ++bad_pkmax;   // both halves of the instruction behave alike
+    }
+    atomicAdd(&counters[4], bad_pkmax);
     atomicAdd(&counters[0], bad_upper);
     atomicAdd(&counters[1], bad_refine);
     atomicMax(&counters[2], (unsigned long long)__float_as_uint(max_err));    // non-negative floats order as ints
@@ -1466,7 +1495,7 @@ __global__ void __launch_bounds__(kThreads) read_probe_kernel(const u32x4* a, ui
 }
 
 __global__ void zero_counters_kernel(unsigned long long* counters) {
-    if (threadIdx.x < 4) counters[threadIdx.x] = 0;
+    if (threadIdx.x < 5) counters[threadIdx.x] = 0;
 }
 
 // ------------------------------------------------------------------------------------------ host side
@@ -1480,11 +1509,11 @@ bool stride_ok(int64_t stride, int32_t V, int64_t rows) {
     return stride >= V && stride <= ((int64_t)1 << 40) && rows <= ((int64_t)1 << 60) / stride;
 }
 
-int env_int(const char* name, int dflt) {
-    const char* s = std::getenv(name);
-    if (!s || !*s) return dflt;
-    return std::atoi(s);
-}
+// Test and tuning hooks (ersd_test_hooks_set); a production process never sets them and no call reads the
+// environment.
+std::atomic<int> g_hook_blocks{0};        // > 0: workgroup count of the race kernels instead of the resident count
+std::atomic<int> g_hook_exhaustive{0};    // != 0: every token scored in fp64 (the reference path inside the kernels)
+std::atomic<int> g_hook_seg_cost{-1};     // >= 0: cost units charged to a row start instead of the built-in figure
 
 bool sizes_ok(int32_t B, int32_t m, int32_t kd, int32_t kt, int32_t V) {
     if (B < 1 || m < 1 || kd < 1 || kt < 1 || V < 1) return false;
@@ -1510,41 +1539,58 @@ bool geometry(int variant, int32_t B, int32_t m, int32_t k_or_N, int32_t V, Geom
     return sizes_ok(g.B, g.m, g.kd, g.kt, g.V);
 }
 
-// Partition for `blocks` resident workgroups (fewer if the job is small).
-Part make_part(const Geometry& g, uint32_t blocks) {
-    Part p;
+// What a workgroup pays for starting another row (measured on an MI355X: a share with two row segments runs 5 to 6
+// us longer than a share with the same bytes in one), in cost units: 10 units are one 8-token group of a row pair,
+// 32 bytes of bf16 or 64 of fp32, and a workgroup streams about 8.5 bytes per nanosecond when all are running.
+constexpr uint32_t kSegCostBf16 = 32000, kSegCostF32 = 16000;
+
+uint32_t seg_cost_for(ersd_dtype dt) {
+    const int h = g_hook_seg_cost.load(std::memory_order_relaxed);
+    if (h >= 0) return (uint32_t)h;
+    return dt == ERSD_BF16 ? kSegCostBf16 : kSegCostF32;
+}
+
+// Partition for `blocks` resident workgroups (fewer if the job is small), with `seg_cost` cost units charged to
+// every row start (less where shares are short: a share is always longer than two such charges).
+Part make_part(const Geometry& g, uint32_t blocks, uint32_t seg_cost) {
+    Part p{};
     p.V8 = (uint32_t)(((int64_t)g.V + 7) / 8);
     p.kd = (uint32_t)g.kd;
     p.kt = (uint32_t)g.kt;
     p.rows = (uint64_t)g.B * g.m * g.kt;
     p.wprefix = nullptr;
-    p.pair_units = (uint64_t)kWPair * p.kd * p.V8;
-    p.Us = p.pair_units + (uint64_t)kWSingle * (p.kt - p.kd) * p.V8;
-    p.U = p.Us * (uint64_t)g.B * g.m;
+    const uint64_t seqs = (uint64_t)g.B * g.m;
+    const uint64_t plain = ((uint64_t)kWPair * p.kd + (uint64_t)kWSingle * (p.kt - p.kd)) * p.V8 * seqs;  // no charges
     uint64_t G = blocks;
-    const uint64_t by_quota = p.U / kMinQuota;
+    const uint64_t by_quota = plain / kMinQuota;
     if (G > by_quota) G = by_quota;
     if (G < 1) G = 1;
     p.G = (uint32_t)G;
-    p.nslot = (uint32_t)((uint64_t)kWPair * p.V8 * p.G / p.U) + 2;
+    const uint64_t cap = plain / G / 2;
+    p.S = (uint32_t)(seg_cost < cap ? seg_cost : cap);
+    p.Lp = p.S + kWPair * p.V8;
+    p.Ls = p.S + kWSingle * p.V8;
+    p.pair_units = (uint64_t)p.Lp * p.kd;
+    p.Us = p.pair_units + (uint64_t)p.Ls * (p.kt - p.kd);
+    p.U = p.Us * seqs;
+    p.nslot = (uint32_t)((uint64_t)p.Lp * p.G / p.U) + 2;
     p.fast = p.U < ((uint64_t)1 << 32) && p.rows < ((uint64_t)1 << 32) && p.U / p.G > p.G ? 1 : 0;
-    p.q = p.r = 0;
-    p.m_G = p.m_q = p.m_Us = p.m_pair_row = p.m_single_row = p.m_kt = 0;
     if (p.fast) {
         p.q = (uint32_t)(p.U / p.G);
         p.r = (uint32_t)(p.U % p.G);
         p.m_G = magic_of(p.G);
         p.m_q = magic_of(p.q);
         p.m_Us = magic_of(p.Us);
-        p.m_pair_row = magic_of((uint64_t)kWPair * p.V8);
-        p.m_single_row = magic_of((uint64_t)kWSingle * p.V8);
+        p.m_pair_row = magic_of(p.Lp);
+        p.m_single_row = magic_of(p.Ls);
         p.m_kt = magic_of(p.kt);
     }
     return p;
 }
 
 size_t workspace_for(const Geometry& g) {
-    const Part p = make_part(g, kMaxBlocks);  // slots per row grow with the workgroup count: size for the most
+    // slots per row grow with the workgroup count and are most when no row start is charged: size for that
+    const Part p = make_part(g, kMaxBlocks, 0);
     return (size_t)p.rows * 2 * p.nslot * sizeof(SegOut);
 }
 
@@ -1578,7 +1624,7 @@ int resident_blocks(K kernel, std::atomic<int>& cache) {
 // Workgroups the race kernel is launched with: as many as are resident at once on the current device.
 int race_blocks(ersd_dtype dt) {
     static std::atomic<int> cache[2];
-    const int forced = env_int("ERSD_FORCE_BLOCKS", 0);  // tests only
+    const int forced = g_hook_blocks.load(std::memory_order_relaxed);
     if (forced > 0) return forced > (int)kMaxBlocks ? (int)kMaxBlocks : forced;
     return dt == ERSD_F32 ? resident_blocks(race_kernel<ERSD_F32>, cache[0])
                           : resident_blocks(race_kernel<ERSD_BF16>, cache[1]);
@@ -1590,13 +1636,14 @@ int plan_part(const Geometry& g, ersd_dtype dt, size_t ws_bytes, Part& p) {
     if (ws_bytes < workspace_for(g)) return ERSD_ERR_WORKSPACE_TOO_SMALL;
     const int blocks = race_blocks(dt);
     if (blocks < 1) return ERSD_ERR_HIP;
-    p = make_part(g, (uint32_t)blocks);
+    p = make_part(g, (uint32_t)blocks, seg_cost_for(dt));
+    if (ws_bytes < (size_t)p.rows * 2 * p.nslot * sizeof(SegOut)) return ERSD_ERR_WORKSPACE_TOO_SMALL;
     return ERSD_OK;
 }
 
 int launch_races(const void* dl, const void* tl, ersd_dtype dt, const Geometry& g, float T, uint64_t seed, void* ws,
                  size_t ws_bytes, void* stream, uint32_t pos0 = 0) {
-    RaceArgs a;
+    RaceArgs a{};
     const int rc = plan_part(g, dt, ws_bytes, a.part);
     if (rc != ERSD_OK) return rc;
     a.draft = static_cast<const char*>(dl);
@@ -1612,8 +1659,7 @@ int launch_races(const void* dl, const void* tl, ersd_dtype dt, const Geometry& 
     a.key1 = (uint32_t)(seed >> 32);
     a.T = (double)T;
     a.c2 = (float)(1.4426950408889634 / (double)T);
-    const char* mode = std::getenv("ERSD_KERNEL");  // tests only: "exhaustive" scores every token in fp64
-    a.exhaustive = mode && std::strcmp(mode, "exhaustive") == 0;
+    a.exhaustive = g_hook_exhaustive.load(std::memory_order_relaxed) != 0;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 grid(a.part.G), block(kThreads);
@@ -1626,7 +1672,7 @@ int launch_finish(int variant, const Geometry& g, ersd_dtype dt, float T, const 
                   int32_t* ttok,
                   int32_t* acc, int32_t* best_draft, int32_t* best_len, int32_t* accept_node, const void* ws,
                   size_t ws_bytes, void* stream) {
-    FinishArgs f;
+    FinishArgs f{};
     const int rc = plan_part(g, dt, ws_bytes, f.part);
     if (rc != ERSD_OK) return rc;
     f.out = static_cast<const SegOut*>(ws);
@@ -1706,7 +1752,7 @@ ArrLayout arrival_layout(int32_t B, int32_t N, int32_t V) {
 
 int arrival_race_blocks(ersd_dtype dt) {
     static std::atomic<int> cache[2];
-    const int forced = env_int("ERSD_FORCE_BLOCKS", 0);  // tests only
+    const int forced = g_hook_blocks.load(std::memory_order_relaxed);
     if (forced > 0) return forced > (int)kMaxBlocks ? (int)kMaxBlocks : forced;
     return dt == ERSD_F32 ? resident_blocks(race_arrivals_kernel<ERSD_F32>, cache[0])
                           : resident_blocks(race_arrivals_kernel<ERSD_BF16>, cache[1]);
@@ -1721,22 +1767,16 @@ int launch_arrival_tree(const void* dl, int64_t qstride, const void* tl, int64_t
     if (blocks < 1) return ERSD_ERR_HIP;
     const ArrLayout l = arrival_layout(B, N, V);
     char* base = static_cast<char*>(ws);
-    ArrMeta meta;
+    ArrMeta meta{};
     meta.valid = reinterpret_cast<int32_t*>(base + l.valid);
     meta.need = reinterpret_cast<int32_t*>(base + l.need);
     meta.wprefix = reinterpret_cast<uint32_t*>(base + l.wprefix);
 
-    Part p;
+    Part p{};                    // plain division (fast == 0): the totals are known on the device only
     p.V8 = (uint32_t)(((int64_t)V + 7) / 8);
     p.kd = 0;                    // no closed-form pair rows: the table decides
     p.kt = (uint32_t)C;
     p.rows = (uint64_t)B * C;
-    p.pair_units = 0;
-    p.Us = 0;                    // filled in on the device from the table
-    p.U = 0;
-    p.fast = 0;                  // plain division: the totals are not known here
-    p.q = p.r = 0;
-    p.m_G = p.m_q = p.m_Us = p.m_pair_row = p.m_single_row = p.m_kt = 0;
     p.G = arrival_blocks(B, C, V, (uint32_t)blocks);
     p.nslot = arrival_nslot(B, C, p.G);
     p.wprefix = meta.wprefix;
@@ -1744,7 +1784,7 @@ int launch_arrival_tree(const void* dl, int64_t qstride, const void* tl, int64_t
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipLaunchKernelGGL(arrival_meta_kernel, dim3(1), dim3(kThreads), 0, s, parent, rank, N, meta);
 
-    RaceArgs a;
+    RaceArgs a{};
     a.draft = static_cast<const char*>(dl);
     a.target = static_cast<const char*>(tl);
     a.out = reinterpret_cast<SegOut*>(base + l.out);
@@ -1761,13 +1801,12 @@ int launch_arrival_tree(const void* dl, int64_t qstride, const void* tl, int64_t
     a.key1 = (uint32_t)(seed >> 32);
     a.T = (double)T;
     a.c2 = (float)(1.4426950408889634 / (double)T);
-    const char* mode = std::getenv("ERSD_KERNEL");  // tests only
-    a.exhaustive = mode && std::strcmp(mode, "exhaustive") == 0;
+    a.exhaustive = g_hook_exhaustive.load(std::memory_order_relaxed) != 0;
     const dim3 grid(p.G), block(kThreads);
     if (dt == ERSD_F32) hipLaunchKernelGGL(race_arrivals_kernel<ERSD_F32>, grid, block, 0, s, a);
     else hipLaunchKernelGGL(race_arrivals_kernel<ERSD_BF16>, grid, block, 0, s, a);
 
-    ArrFinishArgs af;
+    ArrFinishArgs af{};
     af.out = a.out;
     af.outq = a.outq;
     af.target_blocks = (uint32_t)((p.rows + kThreads / 8 - 1) / (kThreads / 8));
@@ -1999,8 +2038,8 @@ int ersd_accept_lengths(int variant, int32_t B, int32_t m, int32_t k_or_N, const
     if (variant == ERSD_VARIANT_MULTI && (!best_draft || !best_len)) return ERSD_ERR_NULL_POINTER;
     Geometry g;
     if (!geometry(variant, B, m, k_or_N, 8, g)) return ERSD_ERR_INVALID_ARG;  // the vocabulary size plays no role
-    FinishArgs f;
-    f.part = make_part(g, 1);
+    FinishArgs f{};
+    f.part = make_part(g, 1, 0);
     f.out = nullptr;
     f.T = 1.0;
     f.m = g.m;
@@ -2038,15 +2077,17 @@ int ersd_selftest_bounds(uint64_t* counters, void* stream) {
     return hipGetLastError() == hipSuccess ? ERSD_OK : ERSD_ERR_HIP;
 }
 
-int ersd_plan_describe_host(int variant, int32_t B, int32_t m, int32_t k_or_N, int32_t V, uint32_t blocks,
-                            uint32_t* out_G, uint32_t* out_nslot, uint64_t* block_start, uint32_t* row_first,
-                            uint32_t* row_last) {
+int ersd_plan_describe_host(int variant, int32_t B, int32_t m, int32_t k_or_N, int32_t V, ersd_dtype dt,
+                            uint32_t blocks, uint32_t* out_G, uint32_t* out_nslot, uint32_t* out_seg_cost,
+                            uint64_t* block_start, uint32_t* row_first, uint32_t* row_last) {
     Geometry g;
     if (!out_G || !out_nslot) return ERSD_ERR_NULL_POINTER;
+    if (dt != ERSD_F32 && dt != ERSD_BF16) return ERSD_ERR_UNSUPPORTED_DTYPE;
     if (blocks < 1 || blocks > kMaxBlocks || !geometry(variant, B, m, k_or_N, V, g)) return ERSD_ERR_INVALID_ARG;
-    const Part p = make_part(g, blocks);
+    const Part p = make_part(g, blocks, seg_cost_for(dt));
     *out_G = p.G;
     *out_nslot = p.nslot;
+    if (out_seg_cost) *out_seg_cost = p.S;
     if (block_start)
         for (uint32_t b = 0; b <= p.G; ++b) {
             const PartPos s = part_start_pos(p, b);
@@ -2081,6 +2122,12 @@ const char* ersd_status_string(int status) {
 }
 
 int ersd_philox_rounds(void) { return kPhiloxRounds; }
+
+void ersd_test_hooks_set(const ersd_test_hooks* h) {
+    g_hook_blocks.store(h ? h->force_blocks : 0);
+    g_hook_exhaustive.store(h ? h->exhaustive : 0);
+    g_hook_seg_cost.store(h ? h->seg_cost_units : -1);
+}
 
 int ersd_version(void) { return 410; }
 

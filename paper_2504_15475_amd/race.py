@@ -61,7 +61,10 @@ def lib():
         L.ersd_race_stage_races.restype = ctypes.c_int
         L.ersd_race_stage_accept.argtypes = [ctypes.c_int, ctypes.c_int, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp,
                                              vp, vp, sz, vp]
-        L.ersd_plan_describe_host.argtypes = [ctypes.c_int, i32, i32, i32, i32, ctypes.c_uint32, vp, vp, vp, vp, vp]
+        L.ersd_plan_describe_host.argtypes = [ctypes.c_int, i32, i32, i32, i32, ctypes.c_int, ctypes.c_uint32, vp, vp, vp,
+                                              vp, vp, vp]
+        L.ersd_test_hooks_set.argtypes = [vp]
+        L.ersd_test_hooks_set.restype = None
         L.ersd_plan_describe_host.restype = ctypes.c_int
         L.ersd_race_stage_accept.restype = ctypes.c_int
         L.ersd_race_sample.argtypes = [vp, ctypes.c_int, i32, i32, i32, i32, i32, f32, u64, vp, vp, sz, vp]
@@ -381,26 +384,41 @@ def read_probe(a, b=None, sink=None):
 
 
 def selftest_bounds(device="cuda"):
-    """Run the device self-check of the filter's fp32 bounds -> dict(bad_upper, bad_refine, max_refine_err, max_upper_slack)."""
-    c = torch.zeros(4, dtype=torch.int64, device=device)
+    """Run the device self-check of the filter's bounds -> dict(bad_upper, bad_refine, max_refine_err,
+    max_upper_slack, bad_pkmax)."""
+    c = torch.zeros(5, dtype=torch.int64, device=device)
     _check(lib().ersd_selftest_bounds(c.data_ptr(), _stream()))
     torch.cuda.synchronize()
     h = c.cpu()
     as_float = lambda v: torch.tensor([int(v)], dtype=torch.int32).view(torch.float32).item()
-    return dict(bad_upper=int(h[0]), bad_refine=int(h[1]), max_refine_err=as_float(h[2]), max_upper_slack=as_float(h[3]))
+    return dict(bad_upper=int(h[0]), bad_refine=int(h[1]), max_refine_err=as_float(h[2]), max_upper_slack=as_float(h[3]),
+                bad_pkmax=int(h[4]))
 
 
-def plan_describe(variant, B, m, k_or_N, V, blocks):
-    """Host-only view of the work partition -> dict(G, nslot, block_start [G+1], row_first [rows], row_last [rows])."""
+def plan_describe(variant, B, m, k_or_N, V, blocks, dtype_code=ERSD_BF16):
+    """Host-only view of the work partition -> dict(G, nslot, seg_cost, block_start [G+1], row_first [rows],
+    row_last [rows])."""
     import numpy as np
     rows = B * (m if variant == VARIANT_MULTI else 1) * (k_or_N if variant == VARIANT_TREE else k_or_N + 1)
-    G, nslot = ctypes.c_uint32(0), ctypes.c_uint32(0)
+    G, nslot, seg = ctypes.c_uint32(0), ctypes.c_uint32(0), ctypes.c_uint32(0)
     start = np.zeros(blocks + 1, dtype=np.uint64)
     first = np.zeros(rows, dtype=np.uint32)
     last = np.zeros(rows, dtype=np.uint32)
-    _check(lib().ersd_plan_describe_host(variant, B, m, k_or_N, V, blocks, ctypes.byref(G), ctypes.byref(nslot),
-                                         start.ctypes.data, first.ctypes.data, last.ctypes.data))
-    return dict(G=G.value, nslot=nslot.value, block_start=start[: G.value + 1], row_first=first, row_last=last)
+    _check(lib().ersd_plan_describe_host(variant, B, m, k_or_N, V, dtype_code, blocks, ctypes.byref(G),
+                                         ctypes.byref(nslot), ctypes.byref(seg), start.ctypes.data, first.ctypes.data,
+                                         last.ctypes.data))
+    return dict(G=G.value, nslot=nslot.value, seg_cost=seg.value, block_start=start[: G.value + 1], row_first=first,
+                row_last=last)
+
+
+class _TestHooks(ctypes.Structure):
+    _fields_ = [("force_blocks", ctypes.c_int32), ("exhaustive", ctypes.c_int32), ("seg_cost_units", ctypes.c_int32)]
+
+
+def set_test_hooks(force_blocks=0, exhaustive=False, seg_cost_units=-1):
+    """Test and tuning hooks of the library (process-wide; no arguments = all defaults)."""
+    h = _TestHooks(int(force_blocks), int(bool(exhaustive)), int(seg_cost_units))
+    lib().ersd_test_hooks_set(ctypes.byref(h))
 
 
 def tree_validate_host(parent):

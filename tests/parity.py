@@ -4,6 +4,27 @@ one of the oracle's tied candidates.  Exempted rows are counted and returned."""
 import numpy as np
 
 
+class _Hooks:
+    """The library's test hooks as one piece of state: set() changes the named fields and applies all of them."""
+
+    DEFAULTS = dict(force_blocks=0, exhaustive=False, seg_cost_units=-1)
+
+    def __init__(self):
+        self.kw = dict(self.DEFAULTS)
+
+    def set(self, **kw):
+        from paper_2504_15475_amd import race
+        self.kw.update(kw)
+        race.set_test_hooks(**self.kw)
+
+    def reset(self):
+        self.kw = dict(self.DEFAULTS)
+        self.set()
+
+
+hooks = _Hooks()
+
+
 def _np(t):
     return t.detach().cpu().numpy() if hasattr(t, "detach") else np.asarray(t)
 

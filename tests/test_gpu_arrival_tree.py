@@ -21,26 +21,24 @@ def race():
 
 @pytest.fixture(autouse=True)
 def clean_env():
-    for k in ("ERSD_FORCE_BLOCKS", "ERSD_KERNEL"):
-        os.environ.pop(k, None)
+    parity.hooks.reset()
     yield
-    for k in ("ERSD_FORCE_BLOCKS", "ERSD_KERNEL"):
-        os.environ.pop(k, None)
+    parity.hooks.reset()
 
 
 def run(race, oracle_mod, draft, target, parent, rank, T, seed, split=0, kernel=None, note=""):
     print(f"[case] arrival tree B={draft.shape[0]} N={len(parent)} V={draft.shape[2]} {draft.dtype} T={T} seed={seed} "
           f"split={split} kernel={kernel} {note}", flush=True)
     if split:
-        os.environ["ERSD_FORCE_BLOCKS"] = str(split)
+        parity.hooks.set(force_blocks=split)
     if kernel:
-        os.environ["ERSD_KERNEL"] = kernel
+        parity.hooks.set(exhaustive=kernel == "exhaustive")
     par_d = torch.as_tensor(np.asarray(parent, dtype=np.int32)).cuda()
     rk_d = torch.as_tensor(np.asarray(rank, dtype=np.int32)).cuda()
     gpu = race.race_verify_arrival_tree(draft, target, par_d, rk_d, T, seed)
     torch.cuda.synchronize()
-    os.environ.pop("ERSD_FORCE_BLOCKS", None)
-    os.environ.pop("ERSD_KERNEL", None)
+    parity.hooks.set(force_blocks=0)
+    parity.hooks.set(exhaustive=False)
     d_host, t_host = draft.cpu(), target.cpu()
     ora = oracle_mod.race_verify_arrival_tree(d_host, t_host, parent, rank, T, seed, max_rank=race.max_rank(),
                                               want_info=True)
@@ -124,10 +122,10 @@ def test_results_do_not_depend_on_the_partition(race):
     ref = None
     for split in (0, 1, 7, 200):
         if split:
-            os.environ["ERSD_FORCE_BLOCKS"] = str(split)
+            parity.hooks.set(force_blocks=split)
         out = race.race_verify_arrival_tree(draft, target, par, rk, 1.0, 1)
         torch.cuda.synchronize()
-        os.environ.pop("ERSD_FORCE_BLOCKS", None)
+        parity.hooks.set(force_blocks=0)
         if ref is None:
             ref = out
         else:

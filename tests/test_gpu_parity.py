@@ -21,19 +21,17 @@ def race():
 
 @pytest.fixture(autouse=True)
 def clean_env():
-    for k in ("ERSD_FORCE_BLOCKS", "ERSD_KERNEL"):
-        os.environ.pop(k, None)
+    parity.hooks.reset()
     yield
-    for k in ("ERSD_FORCE_BLOCKS", "ERSD_KERNEL"):
-        os.environ.pop(k, None)
+    parity.hooks.reset()
 
 
 def run_case(race, oracle_mod, w, split=0, kernel=None, note=""):
     print(f"[case] {wl.describe(w)} split={split} kernel={kernel} {note}", flush=True)
     if split:
-        os.environ["ERSD_FORCE_BLOCKS"] = str(split)
+        parity.hooks.set(force_blocks=split)
     if kernel:
-        os.environ["ERSD_KERNEL"] = kernel
+        parity.hooks.set(exhaustive=kernel == "exhaustive")
     inp = wl.make_inputs(w, "cuda")
     T, seed = w.temperature, w.seed
     d_host, t_host = inp["draft"].cpu(), inp["target"].cpu()
@@ -55,16 +53,17 @@ def run_case(race, oracle_mod, w, split=0, kernel=None, note=""):
         ex = parity.check_tree(gpu, ora, oracle_mod, d_host, t_host, par, T, seed)
     flagged = int(ora["draft_info"]["near_tie"].sum() + ora["target_info"]["near_tie"].sum())
     print(f"[case] ok: oracle near-tie rows {flagged}, exempted rows {ex}", flush=True)
-    os.environ.pop("ERSD_FORCE_BLOCKS", None)
-    os.environ.pop("ERSD_KERNEL", None)
+    parity.hooks.set(force_blocks=0)
+    parity.hooks.set(exhaustive=False)
     return gpu, ora, ex
 
 
 def test_filter_bounds_hold_for_every_generator_word(race):
-    """The streaming filter is exact only if its two fp32 bounds hold; the device checks all 2^32 words."""
+    """The streaming filter is exact only if its two fp32 bounds hold (the device checks all 2^32 words) and if the
+    packed half-precision maximum orders bf16 bit patterns (checked for every pair of in-domain patterns)."""
     r = race.selftest_bounds()
     print(r, flush=True)
-    assert r["bad_upper"] == 0 and r["bad_refine"] == 0
+    assert r["bad_upper"] == 0 and r["bad_refine"] == 0 and r["bad_pkmax"] == 0
     assert r["max_refine_err"] <= 2.0 ** -9
 
 
@@ -95,11 +94,11 @@ def test_results_do_not_depend_on_split_or_kernel_and_are_deterministic(race):
     ref = None
     for split in (0, 1, 2, 5, 19, 300):
         for kernel in (None, "exhaustive"):
-            os.environ["ERSD_FORCE_BLOCKS"] = str(split)
+            parity.hooks.set(force_blocks=split)
             if kernel:
-                os.environ["ERSD_KERNEL"] = kernel
+                parity.hooks.set(exhaustive=kernel == "exhaustive")
             else:
-                os.environ.pop("ERSD_KERNEL", None)
+                parity.hooks.set(exhaustive=False)
             for rep in range(2):
                 out = [x.cpu() for x in race.race_verify(inp["draft"], inp["target"], 1.0, 77)]
                 if ref is None:
@@ -116,10 +115,10 @@ def test_degenerate_rows(race, oracle_mod):
     assert (t == 0).all() and (a == 2).all()
     ninf = torch.full((2, 3, 4104), float("-inf"), device=dev)
     for split in (1, 2, 6):
-        os.environ["ERSD_FORCE_BLOCKS"] = str(split)
+        parity.hooks.set(force_blocks=split)
         d, t, a = race.race_verify(ninf[:, :2].contiguous(), ninf, 1.0, 0)
         assert (t == 0).all() and (d == 0).all() and (a == 2).all()
-    os.environ.pop("ERSD_FORCE_BLOCKS")
+    parity.hooks.set(force_blocks=0)
     g = torch.Generator(device=dev).manual_seed(5)
     V = 30000
     target = 3 * torch.randn(2, 4, V, generator=g, device=dev)
@@ -167,7 +166,7 @@ def test_exact_score_ties_go_to_lowest_index(race, oracle_mod):
     target = row.repeat(1, 2, 1).contiguous().cuda()
     draft = row.repeat(1, 1, 1).contiguous().cuda()
     for split in (1, 9):
-        os.environ["ERSD_FORCE_BLOCKS"] = str(split)
+        parity.hooks.set(force_blocks=split)
         for seed in range(6):
             gpu = race.race_verify(draft, target, 1.0, seed)
             ora = oracle_mod.race_verify(draft.cpu(), target.cpu(), 1.0, seed, want_info=True)

@@ -21,11 +21,9 @@ def race():
 
 @pytest.fixture(autouse=True)
 def clean_env():
-    for k in ("ERSD_FORCE_BLOCKS", "ERSD_KERNEL"):
-        os.environ.pop(k, None)
+    parity.hooks.reset()
     yield
-    for k in ("ERSD_FORCE_BLOCKS", "ERSD_KERNEL"):
-        os.environ.pop(k, None)
+    parity.hooks.reset()
 
 
 def logits(rng, shape, dtype, kind):
@@ -85,9 +83,9 @@ def test_random_case(race, oracle_mod, i):
     rng, V, B, k, m, T, seed, dt = c["rng"], c["V"], c["B"], c["k"], c["m"], c["T"], c["seed"], c["dtype"]
     print("[case] random", {a: b for a, b in c.items() if a != "rng"}, flush=True)
     if c["split"]:
-        os.environ["ERSD_FORCE_BLOCKS"] = str(c["split"])
+        parity.hooks.set(force_blocks=c["split"])
     if c["kernel"]:
-        os.environ["ERSD_KERNEL"] = c["kernel"]
+        parity.hooks.set(exhaustive=c["kernel"] == "exhaustive")
     if c["variant"] == "sequence":
         t_host = logits(rng, (B, k + 1, V), dt, c["kind"])
         d_host = (t_host[:, :k].float() + torch.from_numpy(0.5 * rng.standard_normal((B, k, V)).astype(np.float32))).to(dt)

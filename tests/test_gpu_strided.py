@@ -23,11 +23,9 @@ def race():
 
 @pytest.fixture(autouse=True)
 def clean_env():
-    for k in ("ERSD_FORCE_BLOCKS", "ERSD_KERNEL"):
-        os.environ.pop(k, None)
+    parity.hooks.reset()
     yield
-    for k in ("ERSD_FORCE_BLOCKS", "ERSD_KERNEL"):
-        os.environ.pop(k, None)
+    parity.hooks.reset()
 
 
 def padded(x, pad):
@@ -53,9 +51,9 @@ def test_sequence_rows_with_padding(race, oracle_mod, idx, pads, split, kernel):
     print(f"[case] strided {wl.describe(w)} pads={pads} split={split} kernel={kernel}", flush=True)
     inp = wl.make_inputs(w, "cuda")
     if split:
-        os.environ["ERSD_FORCE_BLOCKS"] = str(split)
+        parity.hooks.set(force_blocks=split)
     if kernel:
-        os.environ["ERSD_KERNEL"] = kernel
+        parity.hooks.set(exhaustive=kernel == "exhaustive")
     ref = race.race_verify(inp["draft"], inp["target"], w.temperature, w.seed)
     out = race.race_verify(padded(inp["draft"], pads[0]), padded(inp["target"], pads[1]), w.temperature, w.seed)
     torch.cuda.synchronize()
@@ -90,7 +88,7 @@ def test_multi_tree_sample_and_arrival_tree_with_padding(race, oracle_mod):
     print(f"[case] strided {wl.describe(w)}", flush=True)
     for split in (0, 5):
         if split:
-            os.environ["ERSD_FORCE_BLOCKS"] = str(split)
+            parity.hooks.set(force_blocks=split)
         ref = race.race_verify_arrival_tree(inp["draft"], inp["target"], inp["parent"], inp["rank"], w.temperature, w.seed)
         out = race.race_verify_arrival_tree(padded(inp["draft"], 13), padded(inp["target"], 2), inp["parent"],
                                             inp["rank"], w.temperature, w.seed)

@@ -1,5 +1,7 @@
 """The balanced work partition, checked on the host by brute force: shares tile the job exactly, every row's
-writers are exactly the shares that overlap it, and the slot bound the workspace is sized for holds."""
+writers are exactly the shares that overlap it, the slot bound the workspace is sized for holds, and the shares
+cost the same under the stated model (10 per group of a row pair, 5 per group of a target-only row, a fixed
+charge per row start)."""
 import numpy as np
 import pytest
 
@@ -15,10 +17,11 @@ CASES = [
 
 
 @pytest.mark.parametrize("variant,B,m,k,V", CASES)
-@pytest.mark.parametrize("blocks", [1, 2, 7, 300, 1792, 2048, 4096])
-def test_partition_invariants(variant, B, m, k, V, blocks):
-    d = race.plan_describe(variant, B, m, k, V, blocks)
-    G, nslot, start = d["G"], d["nslot"], d["block_start"].astype(np.int64)
+@pytest.mark.parametrize("blocks", [1, 2, 7, 300, 768, 1792, 2048, 4096])
+@pytest.mark.parametrize("dt", [race.ERSD_F32, race.ERSD_BF16])
+def test_partition_invariants(variant, B, m, k, V, blocks, dt):
+    d = race.plan_describe(variant, B, m, k, V, blocks, dt)
+    G, nslot, S, start = d["G"], d["nslot"], d["seg_cost"], d["block_start"].astype(np.int64)
     kt = k if variant == TREE else k + 1
     mm = m if variant == MULTI else 1
     rows = B * mm * kt
@@ -32,8 +35,10 @@ def test_partition_invariants(variant, B, m, k, V, blocks):
     assert np.array_equal(first_bf, d["row_first"].astype(np.int64))
     assert np.array_equal(last_bf, d["row_last"].astype(np.int64))
     assert (last_bf - first_bf + 1).max() <= nslot
-    # balance: shares differ by at most one group's worth of cost (weights 10 per pair group, 7 per single)
-    if G > 1 and variant != TREE:
+    # balance: shares differ by at most one group's worth of cost and two row-start charges (a share boundary may
+    # fall inside a charge, which this count gives whole to the share that holds the row's first group)
+    assert S <= (32000 if dt == race.ERSD_BF16 else 16000)
+    if G > 1:
         kd = k
         def cost(lo, hi):      # cost of global groups [lo, hi)
             c = 0
@@ -41,23 +46,24 @@ def test_partition_invariants(variant, B, m, k, V, blocks):
             while pos < hi:
                 row = pos // V8
                 nxt = min(hi, (row + 1) * V8)
-                c += (nxt - pos) * (10 if (row % kt) < kd else 7)
+                c += (nxt - pos) * (10 if (row % kt) < kd else 5) + (S if pos == row * V8 else 0)
                 pos = nxt
             return c
         costs = [cost(int(start[b]), int(start[b + 1])) for b in range(0, G, max(1, G // 50))]
-        assert max(costs) - min(costs) <= 22
+        assert max(costs) - min(costs) <= 22 + 2 * S
+        assert S * 2 <= min(costs) + S
     # the workspace covers the slots of any workgroup count the library may choose
     need = race.workspace_bytes(variant, B, m, k, V, race.ERSD_BF16)
-    assert need >= rows * 2 * nslot * 16
+    assert need >= rows * 2 * nslot * 80
 
 
 def test_plan_rejects_bad_arguments():
     L = race.lib()
     import ctypes
     G, ns = ctypes.c_uint32(), ctypes.c_uint32()
-    assert L.ersd_plan_describe_host(0, 1, 1, 4, 32000, 0, ctypes.byref(G), ctypes.byref(ns), None, None, None) == -2
-    assert L.ersd_plan_describe_host(0, 1, 1, 4, 32000, 5000, ctypes.byref(G), ctypes.byref(ns), None, None, None) == -2
-    assert L.ersd_plan_describe_host(0, 0, 1, 4, 32000, 8, ctypes.byref(G), ctypes.byref(ns), None, None, None) == -2
-    assert L.ersd_plan_describe_host(0, 1, 1, 4, 32000, 8, None, ctypes.byref(ns), None, None, None) == -1
-    assert L.ersd_plan_describe_host(0, 1, 1, 4, 32000, 8, ctypes.byref(G), ctypes.byref(ns), None, None, None) == 0
+    assert L.ersd_plan_describe_host(0, 1, 1, 4, 32000, 0, 0, ctypes.byref(G), ctypes.byref(ns), None, None, None, None) == -2
+    assert L.ersd_plan_describe_host(0, 1, 1, 4, 32000, 0, 5000, ctypes.byref(G), ctypes.byref(ns), None, None, None, None) == -2
+    assert L.ersd_plan_describe_host(0, 0, 1, 4, 32000, 0, 8, ctypes.byref(G), ctypes.byref(ns), None, None, None, None) == -2
+    assert L.ersd_plan_describe_host(0, 1, 1, 4, 32000, 0, 8, None, ctypes.byref(ns), None, None, None, None) == -1
+    assert L.ersd_plan_describe_host(0, 1, 1, 4, 32000, 0, 8, ctypes.byref(G), ctypes.byref(ns), None, None, None, None) == 0
     assert G.value >= 1
