@@ -1,48 +1,166 @@
 #!/usr/bin/env python3
 """Throughput of the exponential-race verification hot path on one MI355X.
 
-One "step" is one pass of the whole hot path (race kernel + acceptance kernel) over one batch of synthetic
-logits that are already resident in HBM.  The default workload is the B=64, k=8, V=128256 bf16 sequence
-configuration the headline metric is quoted on.  Prints ONE JSON line.
+One "step" is one pass of the whole hot path (race kernel + finishing kernel) over one batch of synthetic logits
+that are already resident in HBM.  The headline line is measured on the largest of the benchmark workloads
+(B=256, k=16, V=152064, fp32: 5.14 GB of logits per step); the same run then measures the three other full-size
+workloads (1: sequence bf16, 3: multi-draft bf16, 4: tree bf16) and reports them under "per_workload", each
+with its own step time, race-kernel time, HBM fraction, plain-read figure and oracle check.  Prints ONE JSON line.
 
-The step is issued as its two stages (ersd_race_stage_races, ersd_race_stage_accept -- together exactly
-ersd_race_verify*) so that a HIP event can be recorded between them: the race kernel's own duration is
-measured inside the timed region and priced against the HBM roofline.  Input buffers rotate over several
-distinct sets so that the 256 MB on-die cache cannot serve the reads.
+Timing.  `value` comes from a wall-clock loop over whole steps (the verify entry point), bracketed by device
+synchronisation.  The race kernel's own duration is measured afterwards, in the same process and on the same
+stream, with HIP events around a batch of back-to-back launches of the race stage (ersd_race_stage_races, the first
+of the two stage entry points that together are exactly ersd_race_verify*), at least 20 of them whatever --steps is;
+a second loop brackets single launches for the minimum and the median.  Input buffers rotate over several distinct
+sets so that the 256 MB on-die cache cannot serve the reads.
 """
 import argparse
 import json
-import os
 import sys
 import time
 
 import torch
 
 PEAK_HBM_GBS = 8000.0
+ARITHMETIC = "u32 Philox + f32 bound filter on every token, f64 scores where f32 cannot decide"
 
-# HBM bytes per race-kernel launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a copy
-# kernel of known size; filled in from the summaries under profiles/ (None = not measured for that workload).
-MEASURED_TRAFFIC_BYTES = {1: 286262270, 2: 5171172134, 3: 1118971385, 4: 1068091931}
+# HBM bytes per race-kernel launch from rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE, each scaled by what the same
+# counter reads for a 1 GiB copy); NOT measured in this run: the figures of the summaries under profiles/, which
+# name the commands that produced them.
+PROFILED_TRAFFIC_BYTES = {1: 286262270, 2: 5171172134, 3: 1118971385, 4: 1068091931}
+PROFILE_FILE = {1: "profiles/race_kernel_seq_B64_k8_V128256_bf16.md", 2: "profiles/race_kernel_seq_B256_k16_V152064_f32.md",
+                3: "profiles/race_kernel_multi_B32_m8_k8_V128256_bf16.md", 4: "profiles/race_kernel_tree_B16_N64_V256000_bf16.md"}
+
+
+def make_sets(w, dev, count):
+    """`count` distinct input sets of one workload: set 0 is the workload's own recipe, the others add 1 % noise
+    (a permutation of rows would alias in the cache)."""
+    from paper_2504_15475_amd import workloads as wl
+    base = wl.make_inputs(w, dev)
+    sets = [base]
+    for i in range(1, max(1, count)):
+        g = torch.Generator(device=dev).manual_seed(5000 + i)
+        noise = lambda x: (x.float() + 0.01 * torch.randn(x.shape, generator=g, device=dev)).to(x.dtype).contiguous()
+        s = dict(draft=noise(base["draft"]), target=noise(base["target"]))
+        if "parent" in base:
+            s["parent"] = base["parent"]
+        sets.append(s)
+    return sets
+
+
+def measure_verify(w, sets, args, dev, timed_baseline):
+    """One full-size workload through the verify path -> dict(value, ms_per_step, roofline, check[, cpu_baseline])."""
+    from paper_2504_15475_amd import race, workloads as wl
+    variant = {"sequence": race.VARIANT_SEQUENCE, "multi": race.VARIANT_MULTI, "tree": race.VARIANT_TREE}[w.variant]
+    calls = [race.PreparedVerify(variant, s["draft"], s["target"], w.temperature, w.seed, s.get("parent")) for s in sets]
+    torch.cuda.synchronize()
+    nset = len(calls)
+
+    for i in range(args.warmup):
+        calls[i % nset].run()
+    torch.cuda.synchronize()
+
+    # 1. whole steps, wall clock: the headline throughput
+    K = args.steps
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        calls[i % nset].run()
+    torch.cuda.synchronize()
+    total_s = time.perf_counter() - t0
+    ms_per_step = total_s * 1e3 / K
+
+    # 2. the race kernel alone: HIP events around a batch of back-to-back launches, then around single launches
+    n_ev = max(20, args.event_launches)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def batch(n):
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(n):
+            calls[i % nset].run_races()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    rough = batch(n_ev)  # this measurement's own warm-up (the wall-clock loop above may have been short)
+    n_ev = max(n_ev, min(400, int(20.0 / rough)))  # about 20 ms of launches, so that a short kernel is not timed on 2 ms
+    kernel_ms = batch(n_ev)
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(min(n_ev, 64))]
+    for i, (a0, a1) in enumerate(pairs):
+        a0.record()
+        calls[i % nset].run_races()
+        a1.record()
+        calls[i % nset].run_accept()
+    torch.cuda.synchronize()
+    single = sorted(a0.elapsed_time(a1) for a0, a1 in pairs)
+
+    # 3. context: the same tensors read once by a kernel that does nothing else, with the race kernel's loads and
+    # launch shape, timed the same way
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    for i in range(8):
+        race.read_probe(sets[i % nset]["draft"], sets[i % nset]["target"], sink)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(n_ev):
+        race.read_probe(sets[i % nset]["draft"], sets[i % nset]["target"], sink)
+    e1.record()
+    torch.cuda.synchronize()
+    probe_ms = e0.elapsed_time(e1) / n_ev
+
+    algo_bytes = w.logit_bytes
+    achieved = algo_bytes / (kernel_ms * 1e-3) / 1e9
+    out = {
+        "workload": w.name, "description": wl.describe(w), "race_elements_per_step": w.race_elements,
+        "logit_dtype": "bf16" if w.elem_bytes == 2 else "fp32",
+        "value": w.race_elements * K / total_s, "unit": "elements/s", "steps": K, "ms_per_step": ms_per_step,
+        "roofline": {
+            "bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+            "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": PROFILED_TRAFFIC_BYTES.get(w.index),
+            "traffic_source": (PROFILE_FILE[w.index] + " (rocprofv3 --pmc, not measured in this run)")
+            if w.index in PROFILE_FILE else None,
+            "kernel": "race_kernel", "timing": f"HIP events around {n_ev} back-to-back launches of the race stage",
+            "launches_timed": n_ev, "kernel_ms_avg": round(kernel_ms, 5),
+            "single_launch_ms": {"avg": round(sum(single) / len(single), 5), "min": round(single[0], 5),
+                                 "median": round(single[len(single) // 2], 5),
+                                 "note": "one launch between two events; includes the events' own few microseconds"},
+            "algorithmic_bytes_per_launch": algo_bytes,
+            "whole_step_frac": round(algo_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+            "plain_read_same_shape": {"ms": round(probe_ms, 5), "GB/s": round(algo_bytes / (probe_ms * 1e-3) / 1e9, 1),
+                                      "race_kernel_vs_plain_read": round(probe_ms / kernel_ms, 4)},
+        },
+    }
+    base_out, check = oracle_side(w, sets[0], calls[0], variant, timed_baseline)
+    out["check"] = check
+    if base_out is not None:
+        out["cpu_baseline"] = base_out
+    return out
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", type=int, default=1,
-                    help="index into the five benchmark workloads (default 1); 5 = the tree of workload 4 verified "
-                         "as Algorithm 5 states it (children of a context = first arrivals of one race)")
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", type=int, default=2,
+                    help="index into the five benchmark workloads for the headline line (default 2, the largest); "
+                         "5 = the tree of workload 4 verified as Algorithm 5 states it (children of a context = "
+                         "first arrivals of one race)")
+    ap.add_argument("--also", type=str, default=None,
+                    help="comma-separated workloads measured after the headline one and reported under per_workload "
+                         "(default: 1,3,4 with the default headline workload, none otherwise; '' for none)")
     ap.add_argument("--buffers", type=int, default=4, help="distinct input sets rotated through (cache defeat)")
-    ap.add_argument("--event-every", type=int, default=8,
-                    help="record HIP events around the race kernel of every N-th timed step (events cost a few us)")
-    ap.add_argument("--entry", choices=["verify", "sample", "gsd"], default="verify",
+    ap.add_argument("--event-launches", type=int, default=48,
+                    help="launches of the race kernel timed with HIP events (at least 20 are always timed)")
+    ap.add_argument("--entry", choices=["verify", "sample", "gsd", "calibrate"], default="verify",
                     help="verify: the fused draft+target races (default, the headline metric); sample: the one-model "
                          "entry point on the workload's target logits (how a serving loop calls the race); gsd: the "
-                         "comparison method (ersd_gsd_verify) on the same logits, sequence workloads only")
+                         "comparison method (ersd_gsd_verify) on the same logits, sequence workloads only; calibrate: "
+                         "a plain 1 GiB device-to-device copy, to be run under rocprofv3 --pmc so that the HBM byte "
+                         "counters can be scaled by a kernel of known traffic")
+    ap.add_argument("--npos", type=int, default=0,
+                    help="with --entry sample: positions per call (0 = all target rows at once; 1 = the drafting call)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--fused-call", action="store_true",
-                    help="issue each step through the single verify entry point (no event between the stages)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus must be 1",
@@ -52,114 +170,68 @@ def main():
         print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
         return 2
 
-    from paper_2504_15475_amd import race, workloads as wl
-    race.lib()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.entry == "calibrate":
+        return calibrate(dev)
+    from paper_2504_15475_amd import race, workloads as wl
+    race.lib()
     if args.workload == 5:
         return bench_arrival_tree(args, wl.ARRIVAL_TREE, dev)
     w = wl.WORKLOADS[args.workload]
-    variant = {"sequence": race.VARIANT_SEQUENCE, "multi": race.VARIANT_MULTI, "tree": race.VARIANT_TREE}[w.variant]
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-
     if args.entry == "sample":
         return bench_sample(args, w, dev)
     if args.entry == "gsd":
         return bench_gsd(args, w, dev)
 
-    base = wl.make_inputs(w, dev)
-    sets = [base]
-    for i in range(1, max(1, args.buffers)):
-        # further sets: same distribution, different values (a cheap permutation of rows would alias in cache)
-        g = torch.Generator(device=dev).manual_seed(5000 + i)
-        noise = lambda x: (x.float() + 0.01 * torch.randn(x.shape, generator=g, device=dev)).to(x.dtype).contiguous()
-        s = dict(draft=noise(base["draft"]), target=noise(base["target"]))
-        if "parent" in base:
-            s["parent"] = base["parent"]
-        sets.append(s)
-    calls = [race.PreparedVerify(variant, s["draft"], s["target"], w.temperature, w.seed, s.get("parent")) for s in sets]
+    also = args.also if args.also is not None else ("1,3,4" if args.workload == 2 else "")
+    others = [int(x) for x in also.split(",") if x.strip() != ""]
+
+    # The inputs of every workload of the run are generated first and stay allocated to the end (30 GB for the default
+    # run): memory that a process has freed and allocates again is read measurably slower on this machine (a plain
+    # read of 1.1 GB takes 172 us instead of 165), which would favour whichever workload came first.
+    inputs = {i: make_sets(wl.WORKLOADS[i], dev, args.buffers) for i in [args.workload] + others}
     torch.cuda.synchronize()
-
-    def step(i, mid=None):
-        c = calls[i % len(calls)]
-        if args.fused_call:
-            c.run()
-        else:
-            c.run_stages(mid)
-
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-
-    K = args.steps
-    every = max(1, args.event_every)
-    sampled = [] if args.fused_call else [i for i in range(K) if i % every == every - 1 or K < every]
-    ev0 = {i: torch.cuda.Event(enable_timing=True) for i in sampled}
-    ev1 = {i: torch.cuda.Event(enable_timing=True) for i in sampled}
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(K):
-        if i in ev0:
-            ev0[i].record()
-            step(i, ev1[i])
-        else:
-            step(i)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-
-    total_s = t1 - t0
-    ms_per_step = total_s * 1e3 / K
-    value = w.race_elements * K / total_s
-    if args.fused_call:
-        kernel_ms = None
-    else:
-        durs = sorted(ev0[i].elapsed_time(ev1[i]) for i in sampled)
-        kernel_ms = sum(durs) / len(durs)
-    algo_bytes = w.logit_bytes
-    roofline = None
-    if kernel_ms:
-        achieved = algo_bytes / (kernel_ms * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(w.index),
-                    "kernel": "race_kernel", "launches_timed": len(durs), "kernel_ms_avg": round(kernel_ms, 5),
-                    "kernel_ms_min": round(durs[0], 5), "kernel_ms_median": round(durs[len(durs) // 2], 5),
-                    "algorithmic_bytes_per_launch": algo_bytes}
-
-    if roofline is not None:
-        # context, outside the timed region: the same tensors read once by a kernel that does nothing else, with the
-        # race kernel's loads and launch shape
-        sink = torch.zeros(1, dtype=torch.int32, device=dev)
-        n_probe = 24
-        pe = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_probe)]
-        for i in range(4):
-            race.read_probe(sets[i % len(sets)]["draft"], sets[i % len(sets)]["target"], sink)
-        for i, (e0, e1) in enumerate(pe):
-            e0.record()
-            race.read_probe(sets[i % len(sets)]["draft"], sets[i % len(sets)]["target"], sink)
-            e1.record()
-        torch.cuda.synchronize()
-        probe_ms = sum(e0.elapsed_time(e1) for e0, e1 in pe) / n_probe
-        roofline["plain_read_same_shape"] = {"ms": round(probe_ms, 5),
-                                             "GB/s": round(algo_bytes / (probe_ms * 1e-3) / 1e9, 1),
-                                             "race_kernel_vs_plain_read": round(probe_ms / kernel_ms, 4)}
+    head = measure_verify(w, inputs[args.workload], args, dev, timed_baseline=not args.no_cpu_baseline)
+    per = [measure_verify(wl.WORKLOADS[i], inputs[i], args, dev, timed_baseline=False) for i in others]
 
     out = {
-        "metric": "race_elements_per_sec", "value": value, "unit": "elements/s", "n_gpus": 1, "steps": K,
-        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f64",
-        "data": "synthetic",
-        "config": {"workload": w.name, "description": wl.describe(w), "race_elements_per_step": w.race_elements,
-                   "logit_dtype": "bf16" if w.elem_bytes == 2 else "fp32", "input_buffer_sets": len(calls),
-                   "arithmetic": "u32 Philox + f32 bound filter on every token, f64 scores where f32 cannot decide",
-                   "philox_rounds": race.philox_rounds(),
-                   "issue": "verify entry point" if args.fused_call else "two stage entry points + event"},
-        "roofline": roofline,
+        "metric": "race_elements_per_sec", "value": head["value"], "unit": "elements/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": ARITHMETIC, "data": "synthetic",
+        "config": {"workload": head["workload"], "description": head["description"],
+                   "race_elements_per_step": head["race_elements_per_step"], "logit_dtype": head["logit_dtype"],
+                   "input_buffer_sets": args.buffers, "philox_rounds": race.philox_rounds(),
+                   "issue": "verify entry point (value); race stage entry point (roofline)"},
+        "roofline": head["roofline"],
+        "check": head["check"],
     }
-
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"], out["check"] = cpu_baseline(w, base, calls[0], variant)
+    if "cpu_baseline" in head:
+        out["cpu_baseline"] = head["cpu_baseline"]
+    if per:
+        out["per_workload"] = [
+            {k: x[k] for k in ("workload", "description", "logit_dtype", "race_elements_per_step", "value", "unit",
+                               "ms_per_step", "roofline", "check")} for x in per]
+        fracs = {x["workload"]: x["roofline"]["frac"] for x in [head] + per}
+        out["min_frac"] = {"workload": min(fracs, key=fracs.get), "frac": min(fracs.values()),
+                           "over": "race kernel, the headline workload and per_workload"}
     print(json.dumps(out), flush=True)
+    return 0
+
+
+def calibrate(dev, mib=1024, reps=3):
+    """A device-to-device copy of known size: each copy reads `mib` MiB and writes `mib` MiB, so the ratio of a byte
+    counter's reading for the copy kernel to that size is the scale to apply to the same counter's reading for the
+    race kernel (run this under rocprofv3 --pmc FETCH_SIZE, then WRITE_SIZE)."""
+    n = mib * (1 << 20) // 4
+    src = torch.arange(n, dtype=torch.int32, device=dev)
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    for _ in range(reps):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"entry": "calibrate", "copies": reps, "MiB_read_per_copy": mib, "MiB_written_per_copy": mib}),
+          flush=True)
     return 0
 
 
@@ -200,7 +272,7 @@ def bench_arrival_tree(args, w, dev):
     line = {
         "metric": "race_elements_per_sec", "value": elements * K / total_s, "unit": "elements/s", "n_gpus": 1,
         "steps": K, "warmup": args.warmup, "ms_per_step": total_s * 1e3 / K, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None, "dtype": ARITHMETIC, "data": "synthetic",
         "config": {"workload": w.name, "entry": "ersd_race_verify_arrival_tree", "contexts": B * C, "V": V,
                    "philox_rounds": race.philox_rounds(), "mean_accept_len": float(out[2].float().mean())},
         "roofline": {"bound": "hbm", "achieved": round(nbytes / (gpu_ms * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
@@ -270,7 +342,7 @@ def bench_gsd(args, w, dev):
     print(json.dumps({
         "metric": "race_elements_per_sec", "value": elements * K / total_s, "unit": "elements/s", "n_gpus": 1,
         "steps": K, "warmup": args.warmup, "ms_per_step": total_s * 1e3 / K, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32 normalisers and weights, f64 where f32 cannot decide", "data": "synthetic",
         "config": {"workload": w.name, "entry": "ersd_gsd_verify (comparison method)", "B": B, "k": k, "V": V,
                    "mean_accept_len": float(out[0].float().mean())},
         "roofline": {"bound": "hbm", "achieved": round(nbytes / (gpu_ms * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
@@ -282,26 +354,75 @@ def bench_gsd(args, w, dev):
 
 
 def bench_sample(args, w, dev):
-    """One-model races (ersd_race_sample) on the workload's target logits; events bracket the whole call."""
+    """One-model races (ersd_race_sample).  --npos 0: all target rows of the workload in one call (what verification
+    with separate draft and target calls does).  --npos 1: the drafting call of Algorithm 2, one position of every
+    sequence per call (B x 1 x V), k calls per step, on the workload's draft logits; this call is bound by latency,
+    not bandwidth, and is reported in microseconds per call."""
     from paper_2504_15475_amd import race, workloads as wl
-    base = wl.make_inputs(w, dev)["target"]
+    inputs = wl.make_inputs(w, dev)
+    K = args.steps
+    if args.npos == 1:
+        if w.variant == "tree":
+            print("bench.py: --npos 1 needs a sequence or multi-draft workload", file=sys.stderr)
+            return 2
+        d = inputs["draft"] if w.variant == "multi" else inputs["draft"].unsqueeze(1)      # [B, m, k, V]
+        B, m, k, V = d.shape
+        calls = []
+        for s_ in range(max(1, args.buffers)):
+            src = d if s_ == 0 else (d.float() + 0.01 * torch.randn(d.shape, device=dev)).to(d.dtype)
+            calls.append([race.PreparedSample(src[:, :, j:j + 1].contiguous(), j, w.temperature, w.seed)
+                          for j in range(k)])
+        del d, inputs
+        for i in range(args.warmup):
+            for c in calls[i % len(calls)]:
+                c.run()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for i in range(K):
+            for c in calls[i % len(calls)]:
+                c.run()
+        e1.record()
+        torch.cuda.synchronize()
+        total_s = time.perf_counter() - t0
+        ncalls = K * k
+        gpu_us = e0.elapsed_time(e1) * 1e3 / ncalls
+        elements = B * m * V
+        nbytes = elements * calls[0][0].x.element_size()
+        print(json.dumps({
+            "metric": "race_elements_per_sec", "value": elements * ncalls / total_s, "unit": "elements/s", "n_gpus": 1,
+            "steps": K, "warmup": args.warmup, "ms_per_step": total_s * 1e3 / K, "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": ARITHMETIC, "data": "synthetic",
+            "config": {"workload": w.name + ":draft rows, one position per call", "entry": "ersd_race_sample",
+                       "rows_per_call": B * m, "V": V, "calls_per_step": k, "bytes_per_call": nbytes,
+                       "philox_rounds": race.philox_rounds()},
+            "latency": {"us_per_call_gpu_events": round(gpu_us, 3), "us_per_call_wall": round(total_s * 1e6 / ncalls, 3),
+                        "calls_timed": ncalls,
+                        "note": "events around all calls, issued back to back; two kernels per call (race, resolve)"},
+            "roofline": {"bound": "hbm", "achieved": round(nbytes / (gpu_us * 1e-6) / 1e9, 1), "peak": PEAK_HBM_GBS,
+                         "unit": "GB/s", "frac": round(nbytes / (gpu_us * 1e-6) / 1e9 / PEAK_HBM_GBS, 4), "traffic": None,
+                         "kernel": "race_kernel + resolve_kernel (whole call)", "kernel_ms_avg": round(gpu_us * 1e-3, 6),
+                         "algorithmic_bytes_per_launch": nbytes},
+        }), flush=True)
+        return 0
+
+    base = inputs["target"]
     if w.variant != "multi":
         base = base.unsqueeze(1)
     base = base.contiguous()
     sets = [base] + [(base.float() + 0.01 * torch.randn(base.shape, device=dev)).to(base.dtype).contiguous()
                      for _ in range(max(1, args.buffers) - 1)]
     B, m, npos, V = base.shape
-    need = int(race.lib().ersd_race_sample_workspace_bytes(B, m, npos, V, race._dtype_code(base)))
-    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    calls = [race.PreparedSample(x, 0, w.temperature, w.seed) for x in sets]
     for i in range(args.warmup):
-        race.race_sample(sets[i % len(sets)], 0, w.temperature, w.seed, workspace=ws)
+        calls[i % len(calls)].run()
     torch.cuda.synchronize()
-    K = args.steps
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     e0.record()
     for i in range(K):
-        race.race_sample(sets[i % len(sets)], 0, w.temperature, w.seed, workspace=ws)
+        calls[i % len(calls)].run()
     e1.record()
     torch.cuda.synchronize()
     total_s = time.perf_counter() - t0
@@ -311,7 +432,7 @@ def bench_sample(args, w, dev):
     print(json.dumps({
         "metric": "race_elements_per_sec", "value": elements * K / total_s, "unit": "elements/s", "n_gpus": 1,
         "steps": K, "warmup": args.warmup, "ms_per_step": total_s * 1e3 / K, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None, "dtype": ARITHMETIC, "data": "synthetic",
         "config": {"workload": w.name + ":target rows only", "entry": "ersd_race_sample", "rows": B * m * npos, "V": V,
                    "philox_rounds": race.philox_rounds()},
         "roofline": {"bound": "hbm", "achieved": round(nbytes / (gpu_ms * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
@@ -322,20 +443,20 @@ def bench_sample(args, w, dev):
     return 0
 
 
-def cpu_baseline(w, base, call, variant):
-    """The CPU oracle, as it stands, on a bounded sample of the same inputs, timed on this machine's host cores; its
-    tokens are also compared with the GPU's on that sample."""
+def oracle_side(w, base, call, variant, timed):
+    """The CPU oracle on a bounded sample of the same inputs.  Always: its tokens and accept lengths against the GPU's
+    on that sample.  With `timed`: the oracle, as it stands, run for roughly 15 s of CPU work on this machine's host cores
+    (the reported CPU baseline)."""
     import numpy as np
     import oracle
     from paper_2504_15475_amd import race
-    # sample: leading sequences, repeated so that the oracle does roughly 15 s of CPU work (about 20 ns per token
-    # position and core on this class of host)
+    # sample: leading sequences; about 20 ns per token position and core on this class of host
     per_seq_positions = (w.m * (w.k + 1) if w.variant != "tree" else w.N) * w.V
-    nseq = max(1, min(w.B, int(3.0e8 // per_seq_positions)))
+    nseq = max(1, min(w.B, int((3.0e8 if timed else 1.0e8) // per_seq_positions)))
     d = base["draft"][:nseq].contiguous().cpu()
     t = base["target"][:nseq].contiguous().cpu()
     oracle.race_rows(None, t.reshape(-1, w.V)[0], w.temperature, w.seed)  # warm-up (library load, page-in)
-    passes = max(1, min(50, int(7.5e8 // (per_seq_positions * nseq))))
+    passes = max(1, min(50, int(7.5e8 // (per_seq_positions * nseq)))) if timed else 1
     t0 = time.perf_counter()
     for _ in range(passes):
         if variant == race.VARIANT_SEQUENCE:
@@ -352,11 +473,14 @@ def cpu_baseline(w, base, call, variant):
     mism = int((gpu[0][:nseq] != o["draft_tokens"]).sum() + (gpu[1][:nseq] != o["target_tokens"]).sum())
     mism_acc = int((gpu[2][:nseq] != o["accept_len"]).sum())
     near = int(o["draft_info"]["near_tie"].sum() + o["target_info"]["near_tie"].sum())
+    check = {"sample_sequences": nseq, "of": w.B, "token_mismatches_vs_oracle": mism,
+             "accept_len_mismatches_vs_oracle": mism_acc, "oracle_near_tie_rows": near,
+             "mean_accept_len_gpu": float(np.mean(gpu[2]))}
+    if not timed:
+        return None, check
     base_out = {"value": elements / dt, "unit": "elements/s", "cores": oracle.num_threads(), "kind": "oracle",
                 "sample": f"first {nseq} of {w.B} sequences of the same workload, {passes} passes, {elements} race "
                           f"elements, {dt:.2f} s wall on {oracle.num_threads()} threads"}
-    check = {"sample_sequences": nseq, "token_mismatches_vs_oracle": mism, "accept_len_mismatches_vs_oracle": mism_acc,
-             "oracle_near_tie_rows": near, "mean_accept_len_gpu": float(np.mean(gpu[2]))}
     return base_out, check
 
 

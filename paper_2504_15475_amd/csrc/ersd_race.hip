@@ -1248,40 +1248,64 @@ struct FinishArgs {
 // above all others, by fp64 scores (lowest index on ties) among the contenders otherwise.  Eight adjacent lanes
 // work on one row side, each taking every eighth segment slot; every lane of the wavefront must call this
 // (`active` false for lanes without work) because the lanes of a group meet in shuffles.
-__device__ int32_t resolve_row(const SegOut* o, uint32_t nslots, double T, bool active, int lane8) {
-    // a row rarely has more than eight segments: each lane reads its first slot once and keeps it in registers
-    SegOut mine;
-    mine.count = 0;
-    const bool have = active && (uint32_t)lane8 < nslots;
-    if (have) mine = o[lane8];
-    float lstar = -INFINITY;
-    int32_t total = 0;
-    if (have)
-        for (uint32_t s = lane8; s < nslots; s += 8) {
-            const SegOut so = s == (uint32_t)lane8 ? mine : o[s];
+//
+// A row rarely has more than eight segments: each lane reads its first slot's record once into registers (named
+// fields, no indexed array: nothing goes to scratch memory) and visits it three times; further slots are read again.
+struct MySlots {
+    const SegOut* o;
+    uint32_t nslots;
+    int lane8;
+    int32_t cnt;       // survivors in the lane's first slot, never more than a record holds whatever it says
+    Cand c0, c1, c2, c3;
+
+    __device__ __forceinline__ void load(const SegOut* o_, uint32_t nslots_, bool active, int lane8_) {
+        o = o_;
+        nslots = active ? nslots_ : 0;
+        lane8 = lane8_;
+        cnt = 0;
+        c0 = c1 = c2 = c3 = Cand{};
+        if ((uint32_t)lane8 < nslots) {
+            const SegOut& so = o[lane8];
+            cnt = so.count < kMaxSurvivors ? so.count : kMaxSurvivors;
+            c0 = so.c[0]; c1 = so.c[1]; c2 = so.c[2]; c3 = so.c[3];  // what lies past the count is never looked at
+        }
+    }
+    template <typename F>
+    __device__ __forceinline__ void for_each(F&& f) const {
+        if (cnt > 0) f(c0);
+        if (cnt > 1) f(c1);
+        if (cnt > 2) f(c2);
+        if (cnt > 3) f(c3);
+        for (uint32_t sl = lane8 + 8; sl < nslots; sl += 8) {
+            const int32_t n = o[sl].count;
 #pragma unroll
             for (int32_t k = 0; k < kMaxSurvivors; ++k)
-                if (k < so.count) {
-                    lstar = fmaxf(lstar, so.c[k].s2 - refine_err(so.c[k].s2));
-                    ++total;
-                }
+                if (k < n) f(o[sl].c[k]);
         }
+    }
+};
+
+__device__ int32_t resolve_row(const SegOut* o, uint32_t nslots, double T, bool active, int lane8) {
+    MySlots my;
+    my.load(o, nslots, active, lane8);
+    float lstar = -INFINITY;
+    int32_t total = 0;
+    my.for_each([&](const Cand& cd) {
+        lstar = fmaxf(lstar, cd.s2 - refine_err(cd.s2));
+        ++total;
+    });
 #pragma unroll
     for (int off = 4; off > 0; off >>= 1) {
         lstar = fmaxf(lstar, __shfl_xor(lstar, off, 8));
         total += __shfl_xor(total, off, 8);
     }
     int32_t contenders = 0, only = -1;
-    if (have && total > 0)
-        for (uint32_t s = lane8; s < nslots; s += 8) {
-            const SegOut so = s == (uint32_t)lane8 ? mine : o[s];
-#pragma unroll
-            for (int32_t k = 0; k < kMaxSurvivors; ++k)
-                if (k < so.count && so.c[k].s2 + refine_err(so.c[k].s2) >= lstar) {
-                    ++contenders;
-                    only = so.c[k].idx;
-                }
+    my.for_each([&](const Cand& cd) {
+        if (cd.s2 + refine_err(cd.s2) >= lstar) {
+            ++contenders;
+            only = cd.idx;
         }
+    });
 #pragma unroll
     for (int off = 4; off > 0; off >>= 1) {
         contenders += __shfl_xor(contenders, off, 8);
@@ -1291,17 +1315,12 @@ __device__ int32_t resolve_row(const SegOut* o, uint32_t nslots, double T, bool 
     if (contenders == 1) return only;  // uniform over the eight lanes
     double bs = -INFINITY;
     int32_t bi = -1;
-    if (have)  // fp32 cannot tell: score the contenders exactly
-        for (uint32_t s = lane8; s < nslots; s += 8) {
-            const SegOut so = s == (uint32_t)lane8 ? mine : o[s];
-            for (int32_t k = 0; k < so.count && k < kMaxSurvivors; ++k) {  // never past the record, whatever it holds
-                const Cand cd = so.c[k];
-                if (cd.s2 + refine_err(cd.s2) >= lstar) {
-                    const double sc = exact_score(cd.logit, T, cd.word);
-                    if (bi < 0 || better(sc, cd.idx, bs, bi)) { bs = sc; bi = cd.idx; }
-                }
-            }
+    my.for_each([&](const Cand& cd) {  // fp32 cannot tell: score the contenders exactly
+        if (cd.s2 + refine_err(cd.s2) >= lstar) {
+            const double sc = exact_score(cd.logit, T, cd.word);
+            if (bi < 0 || better(sc, cd.idx, bs, bi)) { bs = sc; bi = cd.idx; }
         }
+    });
 #pragma unroll
     for (int off = 4; off > 0; off >>= 1) {
         const double os = __shfl_xor(bs, off, 8);
@@ -1329,10 +1348,15 @@ __global__ void __launch_bounds__(kThreads) resolve_kernel(FinishArgs f) {
     }
 }
 
+constexpr int kFinishMaxThreads = 1024;        // workgroup size of the one-launch finishing kernel, at most
+constexpr int kFinishMaxItems = 2 * (kFinishMaxThreads / 8);  // (row, side) pairs per prompt it takes: two passes
+
 // Accept lengths of prompt b from its tokens (first disagreement per draft, best draft, or the tree walk).
-// Called by a whole workgroup after the prompt's tokens are visible to it.
-__device__ void accept_prompt(const FinishArgs& f, int32_t b) {
-    const int tid = threadIdx.x;
+// dtok / ttok: the prompt's own tokens, [m][kd] and [m][kt], in global memory or in LDS.  Called by a whole
+// workgroup (of any size up to kFinishMaxThreads) after the tokens are visible to it.
+__device__ void accept_prompt(const FinishArgs& f, int32_t b, const int32_t* dtok, const int32_t* ttok,
+                              const int32_t* parent) {
+    const int tid = threadIdx.x, nthreads = blockDim.x;
     const Part& p = f.part;
     const int32_t kt = (int32_t)p.kt, kd = (int32_t)p.kd;
     const int64_t seq0 = (int64_t)b * f.m;
@@ -1340,16 +1364,14 @@ __device__ void accept_prompt(const FinishArgs& f, int32_t b) {
     if (f.variant == ERSD_VARIANT_TREE) {
         // agree-path depth of every node by walking its ancestors (bounded by the node index)
         const int32_t N = kt;
-        const int32_t* dt = f.draft_tokens + (int64_t)b * N;
-        const int32_t* tt = f.target_tokens + (int64_t)b * N;
         int32_t best_depth = 0, best_node = -1;
-        for (int32_t n = tid; n < N; n += kThreads) {
+        for (int32_t n = tid; n < N; n += nthreads) {
             int32_t depth = 0, cur = n;
             bool ok = true;
             while (true) {
-                if (dt[cur] != tt[cur]) { ok = false; break; }
+                if (dtok[cur] != ttok[cur]) { ok = false; break; }
                 ++depth;
-                const int32_t pa = f.parent[cur];
+                const int32_t pa = parent[cur];
                 if (pa == -1) break;
                 if (pa < 0 || pa >= cur) { ok = false; break; }  // malformed entry; pa < cur bounds the walk
                 cur = pa;
@@ -1364,11 +1386,11 @@ __device__ void accept_prompt(const FinishArgs& f, int32_t b) {
                 best_node = on;
             }
         }
-        __shared__ int32_t wd[kWaves], wn[kWaves];
+        __shared__ int32_t wd[kFinishMaxThreads / kWave], wn[kFinishMaxThreads / kWave];
         if ((tid & (kWave - 1)) == 0) { wd[tid / kWave] = best_depth; wn[tid / kWave] = best_node; }
         __syncthreads();
         if (tid == 0) {
-            for (int w = 1; w < kWaves; ++w)
+            for (int w = 1; w < (nthreads + kWave - 1) / kWave; ++w)
                 if (wd[w] > best_depth || (wd[w] == best_depth && wn[w] >= 0 && (best_node < 0 || wn[w] < best_node))) {
                     best_depth = wd[w];
                     best_node = wn[w];
@@ -1380,20 +1402,34 @@ __device__ void accept_prompt(const FinishArgs& f, int32_t b) {
     }
 
     // sequence / multi: first mismatch per draft
-    for (int32_t d = tid; d < f.m; d += kThreads) {
-        const int32_t* dt = f.draft_tokens + (seq0 + d) * kd;
-        const int32_t* tt = f.target_tokens + (seq0 + d) * kt;
+    __shared__ int32_t best_bits;  // best draft: (accept length << 16 | 0xffff - draft), the largest wins
+    if (tid == 0) best_bits = -1;
+    if (f.best_len) __syncthreads();
+    for (int32_t d = tid; d < f.m; d += nthreads) {
+        const int32_t* dt = dtok + (int64_t)d * kd;
+        const int32_t* tt = ttok + (int64_t)d * kt;
         int32_t acc = 0;
         while (acc < kd && dt[acc] == tt[acc]) ++acc;
         f.accept_len[seq0 + d] = acc;
+        // longest accepted draft, lowest draft index among equals; lengths and draft counts beyond 16 bits take
+        // the sequential path below
+        if (f.best_len && kd < 0x7fff && f.m <= 0xffff) atomicMax(&best_bits, (acc << 16) | (0xffff - d));
     }
     if (f.best_len) {
         __syncthreads();
         if (tid == 0) {
             int32_t bl = -1, bd = -1;
-            for (int32_t d = 0; d < f.m; ++d) {
-                const int32_t v = f.accept_len[seq0 + d];
-                if (v > bl) { bl = v; bd = d; }
+            if (kd < 0x7fff && f.m <= 0xffff) {
+                bl = best_bits >> 16;
+                bd = 0xffff - (best_bits & 0xffff);
+            } else {
+                for (int32_t d = 0; d < f.m; ++d) {
+                    const int32_t* dt = dtok + (int64_t)d * kd;
+                    const int32_t* tt = ttok + (int64_t)d * kt;
+                    int32_t acc = 0;
+                    while (acc < kd && dt[acc] == tt[acc]) ++acc;
+                    if (acc > bl) { bl = acc; bd = d; }
+                }
             }
             f.best_len[b] = bl;
             f.best_draft[b] = bd;
@@ -1402,31 +1438,47 @@ __device__ void accept_prompt(const FinishArgs& f, int32_t b) {
 }
 
 // Accept lengths: one workgroup per prompt b, reading the tokens the previous kernel wrote.
-__global__ void __launch_bounds__(kThreads) accept_kernel(FinishArgs f) { accept_prompt(f, blockIdx.x); }
-
-// Both steps in one launch, for prompts with few rows: workgroup b resolves the rows of prompt b itself.
-__global__ void __launch_bounds__(kThreads) finish_kernel(FinishArgs f) {
+__global__ void __launch_bounds__(kThreads) accept_kernel(FinishArgs f) {
     const int32_t b = blockIdx.x;
-    const int tid = threadIdx.x;
+    accept_prompt(f, b, f.draft_tokens + (int64_t)b * f.m * f.part.kd, f.target_tokens + (int64_t)b * f.m * f.part.kt,
+                  f.parent);
+}
+
+// Both steps in one launch, for prompts with up to kFinishMaxItems (row, side) pairs: workgroup b resolves the rows
+// of prompt b itself, eight lanes per pair, and keeps the tokens in LDS for the acceptance step, so that nothing it
+// wrote to global memory has to come back.
+__global__ void __launch_bounds__(kFinishMaxThreads) finish_kernel(FinishArgs f) {
+    __shared__ int32_t dtok[kFinishMaxItems], ttok[kFinishMaxItems], parent[kFinishMaxItems / 2];
+    const int32_t b = blockIdx.x;
+    const int tid = threadIdx.x, per_pass = blockDim.x / 8;
     const Part& p = f.part;
-    const uint64_t row0 = (uint64_t)b * f.m * p.kt;
-    const uint32_t nitems = (uint32_t)f.m * p.kt * 2;
-    for (uint32_t first = 0; first < nitems; first += kThreads / 8) {  // uniform trip count: lanes meet in shuffles
+    if (f.variant == ERSD_VARIANT_TREE)  // the walk follows parent links: from LDS, not one memory round trip per step
+        for (uint32_t n = tid; n < p.kt; n += blockDim.x) parent[n] = f.parent[n];
+    const uint32_t rows_b = (uint32_t)f.m * p.kt;  // target rows of one prompt
+    const uint64_t row0 = (uint64_t)b * rows_b;
+    const uint32_t nitems = rows_b * 2;
+    for (uint32_t first = 0; first < nitems; first += per_pass) {  // uniform trip count: lanes meet in shuffles
         const uint32_t item = first + (tid >> 3);
-        const uint64_t row = row0 + (item >> 1);
+        const uint32_t lrow = item >> 1;                 // row within the prompt
         const int side = (int)(item & 1);
-        const uint32_t j = (uint32_t)(row % p.kt);
+        const uint32_t j = lrow % p.kt;
         const bool active = item < nitems && (side == 1 || j < p.kd);
-        const uint64_t r = active ? row : row0;
+        const uint64_t r = active ? row0 + lrow : row0;
         const uint32_t n = active ? part_row_slots(p, r) : 0;
         const int32_t tok = resolve_row(f.out + (r * 2 + side) * p.nslot, n, f.T, active, tid & 7);
         if (active && (tid & 7) == 0) {
-            if (side == 1) f.target_tokens[r] = tok;
-            else f.draft_tokens[(r / p.kt) * p.kd + j] = tok;
+            if (side == 1) {
+                f.target_tokens[r] = tok;
+                ttok[lrow] = tok;
+            } else {
+                const uint32_t at = (lrow / p.kt) * p.kd + j;
+                f.draft_tokens[(row0 / p.kt) * p.kd + at] = tok;
+                dtok[at] = tok;
+            }
         }
     }
-    __syncthreads();  // this prompt's tokens were written by this workgroup and are re-read below
-    accept_prompt(f, b);
+    lds_barrier();  // the acceptance step reads the tokens from LDS
+    accept_prompt(f, b, dtok, ttok, parent);
 }
 
 // ------------------------------------------------------------------------------------------ self-check
@@ -1691,8 +1743,11 @@ int launch_finish(int variant, const Geometry& g, ersd_dtype dt, float T, const 
     if (variant < 0) {  // tokens only
         hipLaunchKernelGGL(resolve_kernel, dim3((uint32_t)((items + kThreads / 8 - 1) / (kThreads / 8))),
                            dim3(kThreads), 0, s, f);
-    } else if ((uint64_t)g.m * g.kt * 2 <= 2 * (kThreads / 8)) {  // at most two passes per prompt: one launch
-        hipLaunchKernelGGL(finish_kernel, dim3((uint32_t)g.B), dim3(kThreads), 0, s, f);
+    } else if ((uint64_t)g.m * g.kt * 2 <= (uint64_t)kFinishMaxItems) {  // at most two passes per prompt: one launch
+        // eight lanes per (row, side) pair of a prompt, whole wavefronts, at most kFinishMaxThreads
+        uint32_t threads = (uint32_t)g.m * g.kt * 2 * 8;
+        threads = threads > (uint32_t)kFinishMaxThreads ? (uint32_t)kFinishMaxThreads : (threads + kWave - 1) / kWave * kWave;
+        hipLaunchKernelGGL(finish_kernel, dim3((uint32_t)g.B), dim3(threads), 0, s, f);
     } else {
         hipLaunchKernelGGL(resolve_kernel, dim3((uint32_t)((items + kThreads / 8 - 1) / (kThreads / 8))),
                            dim3(kThreads), 0, s, f);

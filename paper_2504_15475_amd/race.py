@@ -261,6 +261,28 @@ def race_sample(logits, pos0, temperature, seed, workspace=None):
     return tok
 
 
+class PreparedSample:
+    """One ersd_race_sample call with its output and workspace allocated up front (a drafting loop issues one such
+    call per position: little Python work per launch)."""
+
+    def __init__(self, logits, pos0, temperature, seed):
+        x = _dev(logits, "logits")
+        self.x, self.xs, self.code = x, _rows(x, "logits"), _dtype_code(x)
+        self.B, self.m, self.npos, self.V = x.shape
+        self.pos0, self.temperature, self.seed = int(pos0), float(temperature), int(seed)
+        need = int(lib().ersd_race_sample_workspace_bytes(self.B, self.m, self.npos, self.V, self.code))
+        if need == 0:
+            raise ErsdError(-2, status_string(-2))
+        self.ws = torch.empty(need, dtype=torch.uint8, device=x.device)
+        self.tokens = torch.empty((self.B, self.m, self.npos), dtype=torch.int32, device=x.device)
+        self._args = (x.data_ptr(), self.xs, self.code, self.B, self.m, self.npos, self.V, self.pos0, self.temperature,
+                      self.seed, self.tokens.data_ptr(), self.ws.data_ptr(), need)
+
+    def run(self):
+        _check(lib().ersd_race_sample_strided(*self._args, _stream()))
+        return self.tokens
+
+
 def accept_lengths(variant, draft_tokens, target_tokens, parent=None):
     """The acceptance step on token tensors laid out as the verify call of `variant` returns them."""
     d, t = _dev(draft_tokens, "draft_tokens"), _dev(target_tokens, "target_tokens")
@@ -356,18 +378,27 @@ class PreparedVerify:
         _check(rc)
         return self.outputs()
 
-    def run_stages(self, mid_event=None):
+    def run_races(self):
+        """The first stage alone (ersd_race_stage_races): the race kernel."""
         L, p, st = lib(), self._p, _stream()
         _check(L.ersd_race_stage_races(self.variant, p(self.draft), p(self.target), self.code, self.B, self.m, self.kn,
                                        self.V, self.temperature, self.seed, p(self.workspace), self.ws_bytes, st))
-        if mid_event is not None:
-            mid_event.record()
+
+    def run_accept(self):
+        """The second stage alone (ersd_race_stage_accept): the finishing kernels, on what run_races left."""
+        L, p, st = lib(), self._p, _stream()
         _check(L.ersd_race_stage_accept(self.variant, self.code, self.B, self.m, self.kn, self.V, self.temperature,
                                         p(self.parent),
                                         p(self.draft_tokens), p(self.target_tokens), p(self.accept_len),
                                         p(self.best_draft), p(self.best_len), p(self.accept_node), p(self.workspace),
                                         self.ws_bytes, st))
         return self.outputs()
+
+    def run_stages(self, mid_event=None):
+        self.run_races()
+        if mid_event is not None:
+            mid_event.record()
+        return self.run_accept()
 
 
 def read_probe(a, b=None, sink=None):
