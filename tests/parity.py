@@ -1,6 +1,8 @@
 """Comparison of GPU results with the oracle's, to the bar: bit-exact tokens and accept lengths, except at rows
 the oracle flags as near-ties (top-2 scores within 1e-6 relative, not exactly equal), where the GPU token must be
-one of the oracle's tied candidates.  Exempted rows are counted and returned."""
+one of the oracle's tied candidates.  An accept length (and what is derived from it) is exempt only for a sequence
+in which such a deviating row lies at or before the first disagreement of either result; everywhere else it must
+equal the oracle's.  Exempted rows are counted and returned."""
 import numpy as np
 
 
@@ -32,7 +34,7 @@ def _np(t):
 def compare_tokens(name, gpu_tok, info, oracle_mod, row_fetch, temperature, seed, counters):
     """gpu_tok, info: same shape [..]; row_fetch(index_tuple) -> host row; counters(index_tuple) -> (c1, c2, c3)."""
     gpu_tok = _np(gpu_tok)
-    exempt = 0
+    exempt = []
     bad = np.argwhere(gpu_tok != info["token"])
     for ix in map(tuple, bad):
         r = info[ix]
@@ -41,7 +43,7 @@ def compare_tokens(name, gpu_tok, info, oracle_mod, row_fetch, temperature, seed
         c1, c2, c3 = counters(ix)
         cand, n = oracle_mod.row_candidates(row_fetch(ix), temperature, seed, c1, c2, c3)
         assert gpu_tok[ix] in cand.tolist(), f"{name}{ix}: gpu token {gpu_tok[ix]} not among near-tie candidates {cand}"
-        exempt += 1
+        exempt.append(ix)
     return exempt
 
 
@@ -60,16 +62,22 @@ def check_sequence(gpu, ora, oracle_mod, draft_host, target_host, T, seed, multi
         cnt_d = cnt_t = lambda ix: (ix[1], ix[0], 0)
     ex = compare_tokens("draft", dtok, ora["draft_info"], oracle_mod, lambda ix: draft_host[ix], T, seed, cnt_d)
     ex += compare_tokens("target", ttok, ora["target_info"], oracle_mod, lambda ix: target_host[ix], T, seed, cnt_t)
-    # accept lengths: always the leading agreement of the GPU's own tokens, and the oracle's wherever tokens agree
+    # accept lengths: always the leading agreement of the GPU's own tokens; and the oracle's, except for a sequence
+    # with a deviating (near-tied) row at or before the first disagreement of either result
     assert np.array_equal(acc, leading_agreement(dtok, ttok))
-    if ex == 0:
-        assert np.array_equal(acc, ora["accept_len"])
+    oacc = ora["accept_len"]
+    loose = np.zeros(acc.shape, dtype=bool)
+    for ix in ex:
+        seq, j = ix[:-1], ix[-1]
+        if j <= max(acc[seq], oacc[seq]):
+            loose[seq] = True
+    assert np.array_equal(acc[~loose], oacc[~loose])
     if multi:
         bd, bl = _np(gpu[3]), _np(gpu[4])
         assert np.array_equal(bl, acc.max(-1)) and np.array_equal(bd, acc.argmax(-1))
-        if ex == 0:
-            assert np.array_equal(bl, ora["best_len"]) and np.array_equal(bd, ora["best_draft"])
-    return ex
+        strict = ~loose.any(-1)   # a prompt's best draft is exempt if any of its drafts is
+        assert np.array_equal(bl[strict], ora["best_len"][strict]) and np.array_equal(bd[strict], ora["best_draft"][strict])
+    return len(ex)
 
 
 def tree_accept_reference(dtok, ttok, parent):
@@ -100,9 +108,11 @@ def check_tree(gpu, ora, oracle_mod, draft_host, target_host, parent_host, T, se
     ex += compare_tokens("target", ttok, ora["target_info"], oracle_mod, lambda ix: target_host[ix], T, seed, cnt)
     ra, rn = tree_accept_reference(dtok, ttok, np.asarray(parent_host))
     assert np.array_equal(acc, ra) and np.array_equal(node, rn)
-    if ex == 0:
-        assert np.array_equal(acc, ora["accept_len"]) and np.array_equal(node, ora["accept_node"])
-    return ex
+    strict = np.ones(acc.shape, dtype=bool)   # a prompt is exempt only if one of its own nodes deviates
+    for b, _ in ex:
+        strict[b] = False
+    assert np.array_equal(acc[strict], ora["accept_len"][strict]) and np.array_equal(node[strict], ora["accept_node"][strict])
+    return len(ex)
 
 
 def arrival_walk_reference(dtok, ttok, parent, valid):
@@ -137,10 +147,12 @@ def check_arrival_tree(gpu, ora, oracle_mod, target_host, parent_host, rank_host
         assert valid[n] and ora["arrival_near_tie"][b, ctx] == 1, (
             f"draft({b},{n}): gpu {dtok[b, n]} != oracle {ora['draft_tokens'][b, n]} and the arrivals of context "
             f"{ctx} are not near-tied")
-        ex += 1
+        ex.append((b, n))
     ra, rn, re = arrival_walk_reference(dtok, ttok, parent_host, valid)
     assert np.array_equal(acc, ra) and np.array_equal(node, rn) and np.array_equal(emitted, re)
-    if ex == 0:
-        assert np.array_equal(acc, ora["accept_len"]) and np.array_equal(node, ora["accept_node"])
-        assert np.array_equal(emitted, ora["emitted"])
-    return ex
+    strict = np.ones(acc.shape, dtype=bool)   # a prompt is exempt only if one of its own rows deviates
+    for ix in ex:
+        strict[ix[0]] = False
+    assert np.array_equal(acc[strict], ora["accept_len"][strict]) and np.array_equal(node[strict], ora["accept_node"][strict])
+    assert np.array_equal(emitted[strict], ora["emitted"][strict])
+    return len(ex)

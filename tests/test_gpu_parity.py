@@ -154,11 +154,10 @@ def test_adversarial_rows_overflow_the_candidate_list_and_stay_exact(race, oracl
     parity.check_sequence(gpu, ora, oracle_mod, draft.cpu(), target.cpu(), 1.0, 4)
 
 
-def test_exact_score_ties_go_to_lowest_index(race, oracle_mod):
-    """Equal (logit, generator word) pairs give equal scores on both sides; the lower index must win.  Large
-    equal logits on a pair of tokens whose words coincide cannot be constructed without inverting the generator,
-    so the reachable case is used: two equal huge logits dominate any exponential, the race between them is decided
-    by their own words, and the GPU must agree with the oracle including when they sit in different splits."""
+def test_two_equal_dominant_logits_are_decided_by_their_own_words(race, oracle_mod):
+    """Two equal huge logits dominate every exponential, so the race is between those two tokens and is decided by
+    their own generator words; the GPU must agree with the oracle also when they sit in different row segments.
+    (Finite EXACT ties, equal logits with equal words, are the subject of tests/test_gpu_ties.py.)"""
     V = 40960
     row = torch.full((V,), -50.0)
     row[100] = 40.0
