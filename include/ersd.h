@@ -70,10 +70,14 @@ typedef enum {
     ERSD_ERR_UNSUPPORTED_DTYPE = -3,
     ERSD_ERR_MISALIGNED = -4,
     ERSD_ERR_WORKSPACE_TOO_SMALL = -5,
-    ERSD_ERR_HIP = -6
+    ERSD_ERR_HIP = -6,
+    ERSD_ERR_SCRATCH_TOO_SMALL = -7  /* ersd_race_verify_noalloc: the job needs more than ERSD_NOALLOC_SCRATCH_BYTES */
 } ersd_status;
 
 typedef enum { ERSD_VARIANT_SEQUENCE = 0, ERSD_VARIANT_MULTI = 1, ERSD_VARIANT_TREE = 2 } ersd_variant;
+
+/* Scratch memory the library itself holds on every GPU it runs on, for ersd_race_verify_noalloc: 8 MiB. */
+#define ERSD_NOALLOC_SCRATCH_BYTES (8u << 20)
 
 /* Arrival trees (Algorithm 5): largest number of arrivals of one race a tree may use, and largest tree. */
 #define ERSD_MAX_RANK 8
@@ -100,6 +104,26 @@ int ersd_race_verify(const void* draft_logits, const void* target_logits, ersd_d
                      int32_t B, int32_t k, int32_t V, float temperature, uint64_t seed,
                      int32_t* draft_tokens, int32_t* target_tokens, int32_t* accept_len,
                      void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * ersd_race_verify for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation.  Same arguments, results and kernels, without the
+ * workspace: the surviving candidates of the row segments go to a scratch array of ERSD_NOALLOC_SCRATCH_BYTES that
+ * the library holds in device memory (one per GPU, from the moment the library is loaded on it until the process
+ * ends).  The call allocates nothing and frees nothing.
+ *   - A job whose workspace (ersd_race_workspace_bytes) exceeds ERSD_NOALLOC_SCRATCH_BYTES is refused with
+ *     ERSD_ERR_SCRATCH_TOO_SMALL; nothing is enqueued.
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two
+ *     threads) race on it and give unspecified tokens.  Calls on one stream, or ordered by events, are safe; the
+ *     array needs no clearing between calls (every record is written before it is read).
+ *   - The first call on a device looks up the array's device address and the kernels' occupancy (queries, no
+ *     allocation); ersd_noalloc_prepare does the same ahead of time for the current device, e.g. before a graph
+ *     capture begins.  Both return ERSD_ERR_HIP if a query fails.
+ */
+int ersd_race_verify_noalloc(const void* draft_logits, const void* target_logits, ersd_dtype dt,
+                             int32_t B, int32_t k, int32_t V, float temperature, uint64_t seed,
+                             int32_t* draft_tokens, int32_t* target_tokens, int32_t* accept_len, void* stream);
+int ersd_noalloc_prepare(void);
 
 /*
  * m independent draft sequences per prompt (a benchmark workload, not a procedure of the paper: the

@@ -1765,6 +1765,27 @@ int launch(const void* dl, const void* tl, ersd_dtype dt, const Geometry& g, flo
                          stream);
 }
 
+// ---- library-owned scratch memory for the entry point that allocates nothing
+// One array per GPU the library runs on, held until the process ends.  In host code the array's name is only a
+// stand-in for the symbol: the device address comes from hipGetSymbolAddress, asked once per device with that device
+// current, and only that address is ever handed to a kernel.
+constexpr size_t kScratchBytes = (size_t)ERSD_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+int scratch_of_current_device(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return ERSD_ERR_HIP;
+    void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return ERSD_ERR_HIP;
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);  // every thread finds the same address
+    }
+    *out = ptr;
+    return ERSD_OK;
+}
+
 // ---- arrival trees: sizes, workspace layout, launches
 bool arrival_sizes_ok(int32_t B, int32_t N, int32_t V) {
     if (N < 1 || N > kMaxArrNodes) return false;
@@ -2024,6 +2045,30 @@ int ersd_race_verify_tree_strided(const void* draft_logits, int64_t draft_row_st
                       accept_node, workspace, workspace_bytes, stream);
 }
 
+int ersd_noalloc_prepare(void) {
+    void* ptr = nullptr;
+    const int rc = scratch_of_current_device(&ptr);
+    if (rc != ERSD_OK) return rc;
+    if (race_blocks(ERSD_F32) < 1 || race_blocks(ERSD_BF16) < 1) return ERSD_ERR_HIP;  // the occupancy queries, cached
+    return ERSD_OK;
+}
+
+int ersd_race_verify_noalloc(const void* draft_logits, const void* target_logits, ersd_dtype dt, int32_t B, int32_t k,
+                             int32_t V, float temperature, uint64_t seed, int32_t* draft_tokens,
+                             int32_t* target_tokens, int32_t* accept_len, void* stream) {
+    if (!draft_tokens || !target_tokens || !accept_len) return ERSD_ERR_NULL_POINTER;
+    const int rc = check_common(draft_logits, target_logits, dt, temperature, nullptr);
+    if (rc != ERSD_OK) return rc;
+    Geometry g;
+    if (!geometry(ERSD_VARIANT_SEQUENCE, B, 1, k, V, g)) return ERSD_ERR_INVALID_ARG;
+    if (workspace_for(g) > kScratchBytes) return ERSD_ERR_SCRATCH_TOO_SMALL;
+    void* ptr = nullptr;  // the device address of the library's scratch array on the current device
+    const int rs = scratch_of_current_device(&ptr);
+    if (rs != ERSD_OK) return rs;
+    return launch(draft_logits, target_logits, dt, g, temperature, seed, ERSD_VARIANT_SEQUENCE, nullptr, draft_tokens,
+                  target_tokens, accept_len, nullptr, nullptr, nullptr, ptr, kScratchBytes, stream);
+}
+
 int ersd_race_verify(const void* draft_logits, const void* target_logits, ersd_dtype dt, int32_t B, int32_t k,
                      int32_t V, float temperature, uint64_t seed, int32_t* draft_tokens, int32_t* target_tokens,
                      int32_t* accept_len, void* workspace, size_t workspace_bytes, void* stream) {
@@ -2172,6 +2217,7 @@ const char* ersd_status_string(int status) {
         case ERSD_ERR_MISALIGNED: return "pointer not 16-byte aligned";
         case ERSD_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
         case ERSD_ERR_HIP: return "HIP kernel launch failed";
+        case ERSD_ERR_SCRATCH_TOO_SMALL: return "job needs more scratch memory than the allocation-free entry point holds";
         default: return "unknown status";
     }
 }

@@ -63,6 +63,9 @@ def lib():
                                              vp, vp, sz, vp]
         L.ersd_plan_describe_host.argtypes = [ctypes.c_int, i32, i32, i32, i32, ctypes.c_int, ctypes.c_uint32, vp, vp, vp,
                                               vp, vp, vp]
+        L.ersd_race_verify_noalloc.argtypes = [vp, vp, ctypes.c_int, i32, i32, i32, f32, u64, vp, vp, vp, vp]
+        L.ersd_race_verify_noalloc.restype = ctypes.c_int
+        L.ersd_noalloc_prepare.restype = ctypes.c_int
         L.ersd_test_hooks_set.argtypes = [vp]
         L.ersd_test_hooks_set.restype = None
         L.ersd_plan_describe_host.restype = ctypes.c_int
@@ -259,6 +262,31 @@ def race_sample(logits, pos0, temperature, seed, workspace=None):
                                           int(seed), tok.data_ptr(), ws.data_ptr(), ws.numel() * ws.element_size(),
                                           _stream()))
     return tok
+
+
+def race_verify_noalloc(draft_logits, target_logits, temperature, seed, out):
+    """ersd_race_verify_noalloc: no workspace, nothing allocated here either; `out` = (draft_tokens [B,k],
+    target_tokens [B,k+1], accept_len [B]) int32 tensors on the GPU that the caller made earlier."""
+    d, t = _dev(draft_logits, "draft_logits"), _dev(target_logits, "target_logits")
+    if not (d.is_contiguous() and t.is_contiguous()):
+        raise ValueError("logits must be contiguous")
+    code = _dtype_code(d)
+    if _dtype_code(t) != code:
+        raise TypeError("draft and target logits must share a dtype")
+    B, k, V = d.shape
+    if tuple(t.shape) != (B, k + 1, V):
+        raise ValueError(f"target_logits must have shape {(B, k + 1, V)}, got {tuple(t.shape)}")
+    dtok, ttok, acc = out
+    for x, shape in ((dtok, (B, k)), (ttok, (B, k + 1)), (acc, (B,))):
+        if x.dtype != torch.int32 or tuple(x.shape) != shape or not x.is_contiguous() or x.device != d.device:
+            raise ValueError("outputs must be contiguous int32 tensors [B,k], [B,k+1], [B] on the logits' device")
+    _check(lib().ersd_race_verify_noalloc(d.data_ptr(), t.data_ptr(), code, B, k, V, float(temperature), int(seed),
+                                          dtok.data_ptr(), ttok.data_ptr(), acc.data_ptr(), _stream()))
+    return out
+
+
+def noalloc_prepare():
+    _check(lib().ersd_noalloc_prepare())
 
 
 class PreparedSample:

@@ -27,7 +27,8 @@ def test_every_declared_symbol_is_exported(L):
     assert {"ersd_race_verify", "ersd_race_verify_multi", "ersd_race_verify_tree", "ersd_race_workspace_bytes",
             "ersd_status_string", "ersd_version", "ersd_tree_validate_host", "ersd_selftest_bounds",
             "ersd_race_stage_races", "ersd_race_stage_accept", "ersd_plan_describe_host", "ersd_philox_rounds", "ersd_race_sample",
-            "ersd_race_sample_workspace_bytes", "ersd_accept_lengths"} <= set(names)
+            "ersd_race_sample_workspace_bytes", "ersd_accept_lengths", "ersd_race_verify_noalloc", "ersd_noalloc_prepare",
+            "ersd_test_hooks_set"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
 
@@ -37,7 +38,7 @@ def test_version_and_status_strings(L):
     import oracle
     assert L.ersd_philox_rounds() == oracle.get_rounds() and L.ersd_philox_rounds() in (7, 10)   # same generator on both sides
     seen = set()
-    for s in range(0, -7, -1):
+    for s in range(0, -8, -1):
         txt = L.ersd_status_string(s)
         assert txt and txt not in seen
         seen.add(txt)
@@ -263,3 +264,21 @@ def test_binding_row_stride_of_views():
         race._rows(View(x[..., ::2]), "x")                   # vocabulary axis not dense
     y = torch.zeros(5, 64, device="meta").unsqueeze(0)
     assert race._rows(View(y[..., :50]), "y") == 64
+
+
+def test_noalloc_entry_point_checks_its_arguments_on_the_host(L):
+    import ctypes
+    vp, i32 = ctypes.c_void_p, ctypes.c_int32
+    L.ersd_race_verify_noalloc.argtypes = [vp, vp, ctypes.c_int, i32, i32, i32, ctypes.c_float, ctypes.c_uint64, vp, vp,
+                                           vp, vp]
+
+    def call(d=FAKE, t=FAKE, dt=0, B=1, k=2, V=64, T=1.0, o1=FAKE, o2=FAKE, o3=FAKE):
+        return L.ersd_race_verify_noalloc(d, t, dt, B, k, V, T, 0, o1, o2, o3, None)
+
+    assert call(d=None) == -1 and call(o2=None) == -1 and call(dt=5) == -3 and call(T=0.0) == -2 and call(B=0) == -2
+    assert call(d=FAKE + 4) == -4
+    # more scratch than the library holds: refused before any GPU call, with its own status
+    big = dict(dt=0, B=4096, k=16, V=152064)
+    assert L.ersd_race_workspace_bytes(0, big["B"], 1, big["k"], big["V"], 0) > (8 << 20)
+    assert call(**big) == -7
+    assert b"scratch" in L.ersd_status_string(-7)
