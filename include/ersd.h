@@ -194,6 +194,16 @@ int ersd_plan_describe_host(int variant, int32_t B, int32_t m, int32_t k_or_N, i
                             uint64_t* block_start, uint32_t* row_first, uint32_t* row_last);
 
 /*
+ * The same for an arrival tree (ersd_race_verify_arrival_tree), whose partition depends on which contexts have
+ * children: need_host[N + 1] (HOST) holds, per context, the number of arrivals its children ask for (0: no child, the
+ * context's draft row is not read), as the library derives it on the device from (parent, rank).  Rows are the
+ * B * (N + 1) contexts; a context with a draft row costs 10 per group, one without 5.
+ */
+int ersd_arrival_plan_describe_host(int32_t B, int32_t N, int32_t V, const int32_t* need_host, uint32_t blocks,
+                                    uint32_t* out_G, uint32_t* out_nslot, uint64_t* block_start,
+                                    uint32_t* row_first, uint32_t* row_last);
+
+/*
  * Test and tuning hooks: not part of the product interface.  Process-wide settings that the tests use to reach
  * code paths a default launch does not take (a row cut into many segments, the exhaustive scoring path).  A
  * field at its default leaves the library's own choice in place; NULL restores all defaults.
@@ -265,6 +275,29 @@ int ersd_race_verify_arrival_tree(const void* draft_logits, const void* target_l
                                   int32_t* accept_node, int32_t* emitted,
                                   void* workspace, size_t workspace_bytes, void* stream);
 size_t ersd_race_arrival_tree_workspace_bytes(int32_t B, int32_t N, int32_t V, ersd_dtype dt);
+
+/*
+ * The same with the tree's shape derived ahead of time.  A drafting tree is built once and verified against many
+ * steps (Section 4: the optimal tree depends on the acceptance function, not on the step); what the library derives
+ * from (parent, rank) alone, which nodes are valid, how many arrivals every context must deliver, what every
+ * context costs, takes one small kernel that ersd_race_verify_arrival_tree runs on every call.
+ *   ersd_arrival_tree_prepare writes that into `plan` (DEVICE memory of the caller, 16-byte aligned, at least
+ *   ersd_arrival_tree_plan_bytes(N) bytes; enqueued on `stream`).
+ *   ersd_race_verify_arrival_tree_prepared is ersd_race_verify_arrival_tree with row strides (elements between row
+ *   starts, >= V) that reads the plan instead: same arguments otherwise, same results.  The plan must have been
+ *   prepared from the same (parent, rank) and be complete on `stream`'s timeline; it is only read and may serve any
+ *   number of calls, also concurrent ones.
+ */
+size_t ersd_arrival_tree_plan_bytes(int32_t N);
+int ersd_arrival_tree_prepare(const int32_t* parent, const int32_t* rank, int32_t N, void* plan, size_t plan_bytes,
+                              void* stream);
+int ersd_race_verify_arrival_tree_prepared(const void* draft_logits, int64_t draft_row_stride,
+                                           const void* target_logits, int64_t target_row_stride, ersd_dtype dt,
+                                           int32_t B, int32_t N, int32_t V, const int32_t* parent, const int32_t* rank,
+                                           const void* plan, size_t plan_bytes, float temperature, uint64_t seed,
+                                           int32_t* draft_tokens, int32_t* target_tokens, int32_t* accept_len,
+                                           int32_t* accept_node, int32_t* emitted,
+                                           void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * The same calls for logits whose rows do not lie back to back: a head that pads the vocabulary, or a slice

@@ -34,6 +34,7 @@
 #include <cmath>
 #include <cstdint>
 #include <cstring>
+#include <new>
 
 #include "ersd.h"
 #include "ersd_partition.h"
@@ -987,10 +988,13 @@ race_arrivals_kernel(RaceArgs a) {
     uint32_t g0 = first.grp;
     uint64_t seq = first.seq;
     uint32_t j = first.j;  // context
-    while (row < last.row || (row == last.row && g0 < last.grp)) {  // one row segment per trip (workgroup-uniform)
+    // (the first two tests never fail for a partition made by this library; they keep a damaged weight table from
+    // taking the loads out of the tensors)
+    while (row < p.rows && g0 < p.V8 &&
+           (row < last.row || (row == last.row && g0 < last.grp))) {  // one row segment per trip (workgroup-uniform)
         Seg c;
         c.row = row;
-        const uint32_t g1 = row == last.row ? last.grp : p.V8;
+        const uint32_t g1 = row == last.row && last.grp < p.V8 ? last.grp : p.V8;
         c.nq = a.need[j];
         c.prow = a.target + (size_t)row * (size_t)a.pstride * es;
         c.qrow = c.nq > 0 ? a.draft + (size_t)row * (size_t)a.qstride * es : nullptr;
@@ -1001,6 +1005,7 @@ race_arrivals_kernel(RaceArgs a) {
         const int64_t e = (int64_t)g1 * 8;
         c.end = e < a.V ? (int32_t)e : a.V;
         c.slot = g0 == 0 ? 0 : blockIdx.x - part_first_block(p, seq, j);
+        if (c.slot >= p.nslot) break;  // (never for a partition made by this library: keeps the records in the workspace)
         race_segment_arr<DT>(a, c, lds);
         g0 = 0;
         ++row;
@@ -1826,6 +1831,34 @@ ArrLayout arrival_layout(int32_t B, int32_t N, int32_t V) {
     return l;
 }
 
+// A prepared tree shape (ersd_arrival_tree_prepare): valid[N], need[N + 1], wprefix[N + 2], each 16-byte aligned.
+struct PlanLayout {
+    size_t valid, need, wprefix, total;
+};
+PlanLayout plan_layout(int32_t N) {
+    PlanLayout l;
+    l.valid = 0;
+    l.need = align16(l.valid + (size_t)N * sizeof(int32_t));
+    l.wprefix = align16(l.need + (size_t)(N + 1) * sizeof(int32_t));
+    l.total = align16(l.wprefix + (size_t)(N + 2) * sizeof(uint32_t));
+    return l;
+}
+
+// The partition of an arrival tree: every field is set here (the struct is value-initialised, `fast` stays 0: plain
+// division, because the totals are known only where the weight table is), and the table's totals are filled in by
+// part_on_device where the table can be read.
+Part make_arrival_part(int32_t B, int32_t C, int32_t V, uint32_t blocks, const uint32_t* wprefix) {
+    Part p{};
+    p.V8 = (uint32_t)(((int64_t)V + 7) / 8);
+    p.kd = 0;                    // no closed-form pair rows: the table decides
+    p.kt = (uint32_t)C;
+    p.rows = (uint64_t)B * C;
+    p.G = arrival_blocks(B, C, V, blocks);
+    p.nslot = arrival_nslot(B, C, p.G);
+    p.wprefix = wprefix;
+    return p;
+}
+
 int arrival_race_blocks(ersd_dtype dt) {
     static std::atomic<int> cache[2];
     const int forced = g_hook_blocks.load(std::memory_order_relaxed);
@@ -1837,28 +1870,30 @@ int arrival_race_blocks(ersd_dtype dt) {
 int launch_arrival_tree(const void* dl, int64_t qstride, const void* tl, int64_t pstride, ersd_dtype dt, int32_t B,
                         int32_t N, int32_t V,
                         const int32_t* parent, const int32_t* rank, float T, uint64_t seed, int32_t* dtok,
-                        int32_t* ttok, int32_t* acc, int32_t* accept_node, int32_t* emitted, void* ws, void* stream) {
+                        int32_t* ttok, int32_t* acc, int32_t* accept_node, int32_t* emitted, void* ws, void* stream,
+                        const void* plan = nullptr) {
     const int32_t C = N + 1;
     const int blocks = arrival_race_blocks(dt);
     if (blocks < 1) return ERSD_ERR_HIP;
     const ArrLayout l = arrival_layout(B, N, V);
     char* base = static_cast<char*>(ws);
     ArrMeta meta{};
-    meta.valid = reinterpret_cast<int32_t*>(base + l.valid);
-    meta.need = reinterpret_cast<int32_t*>(base + l.need);
-    meta.wprefix = reinterpret_cast<uint32_t*>(base + l.wprefix);
+    if (plan) {  // the tree's shape was derived earlier (ersd_arrival_tree_prepare): read only from here on
+        const PlanLayout pl = plan_layout(N);
+        char* pb = const_cast<char*>(static_cast<const char*>(plan));
+        meta.valid = reinterpret_cast<int32_t*>(pb + pl.valid);
+        meta.need = reinterpret_cast<int32_t*>(pb + pl.need);
+        meta.wprefix = reinterpret_cast<uint32_t*>(pb + pl.wprefix);
+    } else {
+        meta.valid = reinterpret_cast<int32_t*>(base + l.valid);
+        meta.need = reinterpret_cast<int32_t*>(base + l.need);
+        meta.wprefix = reinterpret_cast<uint32_t*>(base + l.wprefix);
+    }
 
-    Part p{};                    // plain division (fast == 0): the totals are known on the device only
-    p.V8 = (uint32_t)(((int64_t)V + 7) / 8);
-    p.kd = 0;                    // no closed-form pair rows: the table decides
-    p.kt = (uint32_t)C;
-    p.rows = (uint64_t)B * C;
-    p.G = arrival_blocks(B, C, V, (uint32_t)blocks);
-    p.nslot = arrival_nslot(B, C, p.G);
-    p.wprefix = meta.wprefix;
+    const Part p = make_arrival_part(B, C, V, (uint32_t)blocks, meta.wprefix);
 
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipLaunchKernelGGL(arrival_meta_kernel, dim3(1), dim3(kThreads), 0, s, parent, rank, N, meta);
+    if (!plan) hipLaunchKernelGGL(arrival_meta_kernel, dim3(1), dim3(kThreads), 0, s, parent, rank, N, meta);
 
     RaceArgs a{};
     a.draft = static_cast<const char*>(dl);
@@ -1931,6 +1966,51 @@ int ersd_race_verify_arrival_tree_strided(const void* draft_logits, int64_t draf
     return launch_arrival_tree(draft_logits, draft_row_stride, target_logits, target_row_stride, dt, B, N, V, parent,
                                rank, temperature, seed, draft_tokens, target_tokens, accept_len, accept_node, emitted,
                                workspace, stream);
+}
+
+size_t ersd_arrival_tree_plan_bytes(int32_t N) {
+    if (N < 1 || N > kMaxArrNodes) return 0;
+    return plan_layout(N).total;
+}
+
+int ersd_arrival_tree_prepare(const int32_t* parent, const int32_t* rank, int32_t N, void* plan, size_t plan_bytes,
+                              void* stream) {
+    if (!parent || !rank || !plan) return ERSD_ERR_NULL_POINTER;
+    if (N < 1 || N > kMaxArrNodes) return ERSD_ERR_INVALID_ARG;
+    if ((uintptr_t)plan & 15) return ERSD_ERR_MISALIGNED;
+    const PlanLayout pl = plan_layout(N);
+    if (plan_bytes < pl.total) return ERSD_ERR_WORKSPACE_TOO_SMALL;
+    char* pb = static_cast<char*>(plan);
+    ArrMeta meta{};
+    meta.valid = reinterpret_cast<int32_t*>(pb + pl.valid);
+    meta.need = reinterpret_cast<int32_t*>(pb + pl.need);
+    meta.wprefix = reinterpret_cast<uint32_t*>(pb + pl.wprefix);
+    hipLaunchKernelGGL(arrival_meta_kernel, dim3(1), dim3(kThreads), 0, static_cast<hipStream_t>(stream), parent, rank,
+                       N, meta);
+    return hipGetLastError() == hipSuccess ? ERSD_OK : ERSD_ERR_HIP;
+}
+
+int ersd_race_verify_arrival_tree_prepared(const void* draft_logits, int64_t draft_row_stride,
+                                           const void* target_logits, int64_t target_row_stride, ersd_dtype dt,
+                                           int32_t B, int32_t N, int32_t V, const int32_t* parent, const int32_t* rank,
+                                           const void* plan, size_t plan_bytes, float temperature, uint64_t seed,
+                                           int32_t* draft_tokens, int32_t* target_tokens, int32_t* accept_len,
+                                           int32_t* accept_node, int32_t* emitted, void* workspace,
+                                           size_t workspace_bytes, void* stream) {
+    if (!parent || !rank || !plan || !draft_tokens || !target_tokens || !accept_len || !accept_node || !emitted ||
+        !workspace)
+        return ERSD_ERR_NULL_POINTER;
+    const int rc = check_common(draft_logits, target_logits, dt, temperature, workspace);
+    if (rc != ERSD_OK) return rc;
+    if ((uintptr_t)plan & 15) return ERSD_ERR_MISALIGNED;
+    if (!arrival_sizes_ok(B, N, V)) return ERSD_ERR_INVALID_ARG;
+    const int64_t rows = (int64_t)B * (N + 1);
+    if (!stride_ok(draft_row_stride, V, rows) || !stride_ok(target_row_stride, V, rows)) return ERSD_ERR_INVALID_ARG;
+    if (workspace_bytes < arrival_layout(B, N, V).total || plan_bytes < plan_layout(N).total)
+        return ERSD_ERR_WORKSPACE_TOO_SMALL;
+    return launch_arrival_tree(draft_logits, draft_row_stride, target_logits, target_row_stride, dt, B, N, V, parent,
+                               rank, temperature, seed, draft_tokens, target_tokens, accept_len, accept_node, emitted,
+                               workspace, stream, plan);
 }
 
 int ersd_race_verify_arrival_tree(const void* draft_logits, const void* target_logits, ersd_dtype dt, int32_t B,
@@ -2198,6 +2278,36 @@ int ersd_plan_describe_host(int variant, int32_t B, int32_t m, int32_t k_or_N, i
             row_first[r] = part_first_block(p, r / p.kt, (uint32_t)(r % p.kt));
             row_last[r] = part_last_block(p, r / p.kt, (uint32_t)(r % p.kt));
         }
+    return ERSD_OK;
+}
+
+int ersd_arrival_plan_describe_host(int32_t B, int32_t N, int32_t V, const int32_t* need_host, uint32_t blocks,
+                                    uint32_t* out_G, uint32_t* out_nslot, uint64_t* block_start, uint32_t* row_first,
+                                    uint32_t* row_last) {
+    if (!need_host || !out_G || !out_nslot) return ERSD_ERR_NULL_POINTER;
+    if (blocks < 1 || blocks > kMaxBlocks || !arrival_sizes_ok(B, N, V)) return ERSD_ERR_INVALID_ARG;
+    const int32_t C = N + 1;
+    // the weight table as the tree-shape kernel writes it: a context with a draft row costs as a pair row
+    uint32_t* wprefix = new (std::nothrow) uint32_t[(size_t)C + 1];
+    if (!wprefix) return ERSD_ERR_INVALID_ARG;
+    wprefix[0] = 0;
+    for (int32_t c = 0; c < C; ++c) wprefix[c + 1] = wprefix[c] + (need_host[c] > 0 ? kWPair : kWSingle);
+    Part p = make_arrival_part(B, C, V, blocks, wprefix);
+    p.Us = (uint64_t)wprefix[C] * p.V8;   // what part_on_device reads from the table
+    p.U = p.Us * (uint64_t)B;
+    *out_G = p.G;
+    *out_nslot = p.nslot;
+    if (block_start)
+        for (uint32_t b = 0; b <= p.G; ++b) {
+            const PartPos s = part_start_pos(p, b);
+            block_start[b] = s.row * p.V8 + s.grp;
+        }
+    if (row_first && row_last)
+        for (uint64_t r = 0; r < p.rows; ++r) {
+            row_first[r] = part_first_block(p, r / p.kt, (uint32_t)(r % p.kt));
+            row_last[r] = part_last_block(p, r / p.kt, (uint32_t)(r % p.kt));
+        }
+    delete[] wprefix;
     return ERSD_OK;
 }
 

@@ -470,6 +470,23 @@ def plan_describe(variant, B, m, k_or_N, V, blocks, dtype_code=ERSD_BF16):
                 row_last=last)
 
 
+def arrival_plan_describe(B, N, V, need, blocks):
+    """Host-only view of an arrival tree's work partition; need: int32 [N+1] host array (arrivals per context)."""
+    import numpy as np
+    need = np.ascontiguousarray(np.asarray(need, dtype=np.int32))
+    rows = B * (N + 1)
+    G, nslot = ctypes.c_uint32(0), ctypes.c_uint32(0)
+    start = np.zeros(blocks + 1, dtype=np.uint64)
+    first = np.zeros(rows, dtype=np.uint32)
+    last = np.zeros(rows, dtype=np.uint32)
+    L = lib()
+    L.ersd_arrival_plan_describe_host.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
+                                                  ctypes.c_uint32] + [ctypes.c_void_p] * 5
+    _check(L.ersd_arrival_plan_describe_host(B, N, V, need.ctypes.data, blocks, ctypes.byref(G), ctypes.byref(nslot),
+                                             start.ctypes.data, first.ctypes.data, last.ctypes.data))
+    return dict(G=G.value, nslot=nslot.value, block_start=start[: G.value + 1], row_first=first, row_last=last)
+
+
 class _TestHooks(ctypes.Structure):
     _fields_ = [("force_blocks", ctypes.c_int32), ("exhaustive", ctypes.c_int32), ("seg_cost_units", ctypes.c_int32)]
 
@@ -495,8 +512,28 @@ def arrival_tree_workspace_bytes(B, N, V, dtype_code):
     return int(lib().ersd_race_arrival_tree_workspace_bytes(B, N, V, dtype_code))
 
 
-def race_verify_arrival_tree(draft_logits, target_logits, parent, rank, temperature, seed, workspace=None):
-    """Algorithm 5.  draft, target [B,N+1,V] (one row per context); parent, rank int32 [N] on the GPU.
+def arrival_tree_prepare(parent, rank):
+    """Derive a tree's shape once (ersd_arrival_tree_prepare) -> plan tensor for race_verify_arrival_tree(plan=...)."""
+    par, rk = _dev(parent, "parent"), _dev(rank, "rank")
+    N = par.shape[0]
+    if par.dtype != torch.int32 or rk.dtype != torch.int32 or tuple(rk.shape) != (N,):
+        raise ValueError("parent and rank must be int32 [N]")
+    L = lib()
+    L.ersd_arrival_tree_plan_bytes.argtypes = [ctypes.c_int32]
+    L.ersd_arrival_tree_plan_bytes.restype = ctypes.c_size_t
+    need = int(L.ersd_arrival_tree_plan_bytes(N))
+    if need == 0:
+        raise ErsdError(-2, status_string(-2))
+    plan = torch.empty(need, dtype=torch.uint8, device=par.device)
+    L.ersd_arrival_tree_prepare.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p,
+                                            ctypes.c_size_t, ctypes.c_void_p]
+    _check(L.ersd_arrival_tree_prepare(par.data_ptr(), rk.data_ptr(), N, plan.data_ptr(), need, _stream()))
+    return plan
+
+
+def race_verify_arrival_tree(draft_logits, target_logits, parent, rank, temperature, seed, workspace=None, plan=None):
+    """Algorithm 5.  draft, target [B,N+1,V] (one row per context); parent, rank int32 [N] on the GPU; plan: what
+    arrival_tree_prepare(parent, rank) returned, or None to derive the tree's shape in this call.
 
     -> (draft_tokens [B,N], target_tokens [B,N+1], accept_len [B], accept_node [B], emitted [B,N+1])
     """
@@ -522,6 +559,19 @@ def race_verify_arrival_tree(draft_logits, target_logits, parent, rank, temperat
     acc = torch.empty((B,), dtype=torch.int32, device=d.device)
     node = torch.empty((B,), dtype=torch.int32, device=d.device)
     emitted = torch.empty((B, C), dtype=torch.int32, device=d.device)
+    if plan is not None:
+        L = lib()
+        vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+        L.ersd_race_verify_arrival_tree_prepared.argtypes = [vp, i64, vp, i64, ctypes.c_int, i32, i32, i32, vp, vp, vp,
+                                                             sz, ctypes.c_float, ctypes.c_uint64, vp, vp, vp, vp, vp,
+                                                             vp, sz, vp]
+        _dev(plan, "plan")
+        _check(L.ersd_race_verify_arrival_tree_prepared(
+            d.data_ptr(), ds, t.data_ptr(), ts, code, B, N, V, par.data_ptr(), rk.data_ptr(), plan.data_ptr(),
+            plan.numel() * plan.element_size(), float(temperature), int(seed), dtok.data_ptr(), ttok.data_ptr(),
+            acc.data_ptr(), node.data_ptr(), emitted.data_ptr(), workspace.data_ptr(),
+            workspace.numel() * workspace.element_size(), _stream()))
+        return dtok, ttok, acc, node, emitted
     _check(lib().ersd_race_verify_arrival_tree_strided(d.data_ptr(), ds, t.data_ptr(), ts, code, B, N, V,
                                                        par.data_ptr(), rk.data_ptr(), float(temperature), int(seed),
                                                        dtok.data_ptr(), ttok.data_ptr(), acc.data_ptr(),

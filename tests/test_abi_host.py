@@ -282,3 +282,28 @@ def test_noalloc_entry_point_checks_its_arguments_on_the_host(L):
     assert L.ersd_race_workspace_bytes(0, big["B"], 1, big["k"], big["V"], 0) > (8 << 20)
     assert call(**big) == -7
     assert b"scratch" in L.ersd_status_string(-7)
+
+
+def test_prepared_arrival_tree_entry_points_check_their_arguments_on_the_host(L):
+    import ctypes
+    vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+    L.ersd_arrival_tree_plan_bytes.argtypes = [i32]
+    L.ersd_arrival_tree_plan_bytes.restype = sz
+    assert L.ersd_arrival_tree_plan_bytes(0) == 0 and L.ersd_arrival_tree_plan_bytes(8193) == 0
+    need = L.ersd_arrival_tree_plan_bytes(64)
+    assert need >= 4 * (64 + 65 + 66) and need % 16 == 0
+    L.ersd_arrival_tree_prepare.argtypes = [vp, vp, i32, vp, sz, vp]
+    assert L.ersd_arrival_tree_prepare(None, FAKE, 64, FAKE, need, None) == -1
+    assert L.ersd_arrival_tree_prepare(FAKE, FAKE, 64, None, need, None) == -1
+    assert L.ersd_arrival_tree_prepare(FAKE, FAKE, 0, FAKE, need, None) == -2
+    assert L.ersd_arrival_tree_prepare(FAKE, FAKE, 64, FAKE + 8, need, None) == -4
+    assert L.ersd_arrival_tree_prepare(FAKE, FAKE, 64, FAKE, need - 1, None) == -5
+    L.ersd_race_verify_arrival_tree_prepared.argtypes = [vp, i64, vp, i64, ctypes.c_int, i32, i32, i32, vp, vp, vp, sz,
+                                                         ctypes.c_float, ctypes.c_uint64, vp, vp, vp, vp, vp, vp, sz, vp]
+
+    def call(d=FAKE, plan=FAKE, pb=need, B=2, N=64, V=1000, stride=1000, T=1.0, ws=FAKE, wsb=1 << 30):
+        return L.ersd_race_verify_arrival_tree_prepared(d, stride, FAKE, stride, 0, B, N, V, FAKE, FAKE, plan, pb, T, 0,
+                                                        FAKE, FAKE, FAKE, FAKE, FAKE, ws, wsb, None)
+
+    assert call(d=None) == -1 and call(plan=None) == -1 and call(plan=FAKE + 4) == -4 and call(T=-1.0) == -2
+    assert call(N=0) == -2 and call(stride=999) == -2 and call(pb=need - 16) == -5 and call(wsb=64) == -5

@@ -36,7 +36,12 @@ def run(race, oracle_mod, draft, target, parent, rank, T, seed, split=0, kernel=
     par_d = torch.as_tensor(np.asarray(parent, dtype=np.int32)).cuda()
     rk_d = torch.as_tensor(np.asarray(rank, dtype=np.int32)).cuda()
     gpu = race.race_verify_arrival_tree(draft, target, par_d, rk_d, T, seed)
+    # the same through a tree shape prepared ahead of time: identical outputs
+    plan = race.arrival_tree_prepare(par_d, rk_d)
+    again = race.race_verify_arrival_tree(draft, target, par_d, rk_d, T, seed, plan=plan)
     torch.cuda.synchronize()
+    for a, b in zip(gpu, again):
+        assert torch.equal(a, b)
     parity.hooks.set(force_blocks=0)
     parity.hooks.set(exhaustive=False)
     d_host, t_host = draft.cpu(), target.cpu()

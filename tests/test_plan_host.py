@@ -67,3 +67,55 @@ def test_plan_rejects_bad_arguments():
     assert L.ersd_plan_describe_host(0, 1, 1, 4, 32000, 0, 8, None, ctypes.byref(ns), None, None, None, None) == -1
     assert L.ersd_plan_describe_host(0, 1, 1, 4, 32000, 0, 8, ctypes.byref(G), ctypes.byref(ns), None, None, None, None) == 0
     assert G.value >= 1
+
+
+def _random_tree(rng, N, branching):
+    """(parent, rank) with up to `branching` children per context, some nodes malformed on purpose."""
+    parent = np.full(N, -1, dtype=np.int32)
+    rank = np.zeros(N, dtype=np.int32)
+    used = {}
+    for n in range(N):
+        p = int(rng.integers(-1, n)) if n else -1
+        r = used.get(p, 0)
+        used[p] = r + 1
+        parent[n], rank[n] = p, min(r, 7) if r < branching else int(rng.integers(0, 8))
+    for n in rng.integers(0, N, size=max(1, N // 10)):      # malformed entries: parent >= node, rank out of range
+        if rng.random() < 0.5:
+            parent[n] = int(rng.integers(n, N + 3))
+        else:
+            rank[n] = int(rng.integers(8, 12))
+    return parent, rank
+
+
+@pytest.mark.parametrize("B,N,V", [(16, 64, 256000), (3, 12, 1000), (1, 1, 8), (2, 700, 4999), (5, 3, 100001),
+                                   (4, 2500, 32000)])
+@pytest.mark.parametrize("blocks", [1, 2, 7, 300, 768, 4096])
+def test_arrival_tree_partition_stays_inside_the_job(oracle_mod, B, N, V, blocks):
+    """The arrival tree's partition is evaluated on the device from a weight table that only exists there; here the
+    same functions run on the host over a table built from the oracle's reading of the tree (which contexts have
+    children), and every share, every row's writers and the slot bound are checked by brute force."""
+    rng = np.random.default_rng(N * 131 + B)
+    for trial in range(3):
+        parent, rank = _random_tree(rng, N, branching=int(rng.integers(1, 5)))
+        _, need = oracle_mod.arrival_tree_shape(parent, rank, 8)
+        d = race.arrival_plan_describe(B, N, V, need, blocks)
+        G, nslot, start = d["G"], d["nslot"], d["block_start"].astype(np.int64)
+        rows, V8 = B * (N + 1), (V + 7) // 8
+        assert 1 <= G <= blocks and len(start) == G + 1
+        assert start[0] == 0 and start[-1] == rows * V8 and (np.diff(start) > 0).all()
+        first_bf = np.searchsorted(start, np.arange(rows) * V8, side="right") - 1
+        last_bf = np.searchsorted(start, (np.arange(rows) + 1) * V8 - 1, side="right") - 1
+        assert np.array_equal(first_bf, d["row_first"].astype(np.int64))
+        assert np.array_equal(last_bf, d["row_last"].astype(np.int64))
+        assert (last_bf - first_bf + 1).max() <= nslot
+        # shares cost the same: 10 per group of a context with a draft row, 5 otherwise
+        w = np.where(np.tile(need, B) > 0, 10, 5).astype(np.int64)
+        cum = np.concatenate([[0], np.cumsum(w * V8)])
+        def units(g):           # cost units before global group g
+            r = np.minimum(g // V8, rows - 1)
+            return np.where(g >= rows * V8, cum[-1], cum[r] + (g - r * V8) * w[r])
+        costs = np.diff(units(start))
+        assert costs.max() - costs.min() <= 22
+        # the workspace covers these slots
+        for code in (race.ERSD_F32, race.ERSD_BF16):
+            assert race.arrival_tree_workspace_bytes(B, N, V, code) >= rows * (2 * 80 + 272) * nslot
