@@ -74,7 +74,7 @@ def test_exact_ties_go_to_the_lowest_index(oracle_mod):
     draft, target = _seq(rng, 1, 1, 200)
     info = oracle_mod.race_rows(draft[0, 0], target[0, 0], 1.0, 9, 0, 0, 0)
     for s, row in ((0, draft[0, 0]), (1, target[0, 0])):
-        e = mini_oracle.exponentials(200, 9, 0, 0, 0)
+        e = mini_oracle.exponentials(200, 9, 0, 0, 0, rounds=oracle_mod.get_rounds())
         scores = row.astype(np.float64) - np.log(e)
         assert info[s]["token"] == int(np.argmax(scores))
         assert info[s]["s1"] == pytest.approx(scores.max(), rel=1e-14)
@@ -185,7 +185,7 @@ def test_malformed_parent_entries_reject_the_node(oracle_mod):
 def test_near_tie_flags_and_candidate_sets(oracle_mod):
     V = 64
     row = np.zeros(V, dtype=np.float32)
-    e = mini_oracle.exponentials(V, 55, 0, 0, 0)
+    e = mini_oracle.exponentials(V, 55, 0, 0, 0, rounds=oracle_mod.get_rounds())
     g = -np.log(e)
     order = np.argsort(-g)
     a, b = int(order[0]), int(order[1])

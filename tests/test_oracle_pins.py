@@ -101,7 +101,8 @@ def test_log_form_equals_literal_argmin_form(oracle_mod):
         draft = (target[:, :k] + rng.normal(0, 0.8, size=(2, k, V))).astype(np.float32)
         seed = int(rng.integers(0, 2**63))
         o = oracle_mod.race_verify(draft, target, T, seed)
-        dt, tt, acc = mini_oracle.race_verify(draft.astype(np.float64), target.astype(np.float64), T, seed)
+        dt, tt, acc = mini_oracle.race_verify(draft.astype(np.float64), target.astype(np.float64), T, seed,
+                                               rounds=oracle_mod.get_rounds())
         assert np.array_equal(o["draft_tokens"], dt)
         assert np.array_equal(o["target_tokens"], tt)
         assert np.array_equal(o["accept_len"], acc)
@@ -113,7 +114,8 @@ def test_bf16_rows_are_widened_exactly(oracle_mod):
     bits_t = (rng.normal(0, 3, size=(1, k + 1, V)).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
     bits_d = (rng.normal(0, 3, size=(1, k, V)).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
     o = oracle_mod.race_verify(bits_d, bits_t, 1.0, 99)
-    dt, tt, acc = mini_oracle.race_verify(mini_oracle.bf16_to_f64(bits_d), mini_oracle.bf16_to_f64(bits_t), 1.0, 99)
+    dt, tt, acc = mini_oracle.race_verify(mini_oracle.bf16_to_f64(bits_d), mini_oracle.bf16_to_f64(bits_t), 1.0, 99,
+                                           rounds=oracle_mod.get_rounds())
     assert np.array_equal(o["draft_tokens"], dt) and np.array_equal(o["target_tokens"], tt)
     assert np.array_equal(o["accept_len"], acc)
     # and the same values given as fp32 must give the same answer
