@@ -72,7 +72,8 @@ def lib():
         L.oracle_race_verify_arrival_tree.restype = ctypes.c_int
         L.oracle_arrival_tree_shape.argtypes = [vp, vp, i32, i32, vp, vp]
         L.oracle_arrival_tree_shape.restype = None
-        L.oracle_gsd_verify.argtypes = [vp, vp, ctypes.c_int, i32, i32, i64, vp, f32, u64, vp, vp, vp]
+        L.oracle_gsd_verify.argtypes = [vp, vp, ctypes.c_int, i32, i32, i64, vp, f32, u64, vp, vp, vp, ctypes.c_double,
+                                        ctypes.c_double]
         L.oracle_gsd_verify.restype = ctypes.c_int
         L.oracle_logsumexp.argtypes = [vp, ctypes.c_int, i64, f32]
         L.oracle_logsumexp.restype = ctypes.c_double
@@ -300,7 +301,7 @@ def race_verify_arrival_tree(draft, target, parent, rank, temperature, seed, max
 
 
 GSD_INFO_DTYPE = np.dtype([("near_accept", "<i4"), ("rivals", "<i4"), ("lse_p", "<f8"), ("lse_q", "<f8"),
-                           ("score", "<f8")], align=True)
+                           ("score", "<f8"), ("min_accept_gap", "<f8")], align=True)
 
 
 def logsumexp(row, temperature):
@@ -312,8 +313,10 @@ def gsd_uniform(seed, j, b):
     return lib().oracle_gsd_uniform(int(seed), int(j), int(b))
 
 
-def gsd_verify(draft, target, draft_tokens, temperature, seed, want_info=False):
-    """GSD sequence verification: draft [B,k,V], target [B,k+1,V], draft_tokens [B,k] -> dict(accept_len, next_token)."""
+def gsd_verify(draft, target, draft_tokens, temperature, seed, want_info=False, accept_rel_tol=0.0,
+               weight_rel_tol=0.0):
+    """GSD sequence verification: draft [B,k,V], target [B,k+1,V], draft_tokens [B,k] -> dict(accept_len, next_token).
+    The two tolerances only shape the sensitivity report in `info` (near_accept, rivals), never the results."""
     d, dt = _host(draft)
     t, dt2 = _host(target)
     assert dt == dt2
@@ -325,7 +328,8 @@ def gsd_verify(draft, target, draft_tokens, temperature, seed, want_info=False):
     nxt = np.zeros(B, dtype=np.int32)
     info = np.zeros(B, dtype=GSD_INFO_DTYPE) if want_info else None
     rc = lib().oracle_gsd_verify(_ptr(d), _ptr(t), dt, B, k, V, _ptr(tok), float(temperature), int(seed), _ptr(acc),
-                                 _ptr(nxt), _ptr(info) if want_info else None)
+                                 _ptr(nxt), _ptr(info) if want_info else None, float(accept_rel_tol),
+                                 float(weight_rel_tol))
     if rc != 0:
         raise ValueError("oracle_gsd_verify: invalid arguments")
     out = dict(accept_len=acc, next_token=nxt)

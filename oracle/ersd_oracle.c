@@ -453,7 +453,8 @@ double oracle_gsd_uniform(uint64_t seed, uint32_t j, uint32_t b) {
 
 int oracle_gsd_verify(const void* draft, const void* target, int dtype, int32_t B, int32_t k, int64_t V,
                       const int32_t* draft_tokens, float temperature, uint64_t seed,
-                      int32_t* accept_len, int32_t* next_token, oracle_gsd_info* info) {
+                      int32_t* accept_len, int32_t* next_token, oracle_gsd_info* info, double accept_rel_tol,
+                      double weight_rel_tol) {
     if (bad_common(draft, target, dtype, V, temperature)) return -1;
     if (B < 1 || k < 1 || !draft_tokens || !accept_len || !next_token) return -1;
     for (int64_t t = 0; t < (int64_t)B * k; ++t)
@@ -471,6 +472,7 @@ int oracle_gsd_verify(const void* draft, const void* target, int dtype, int32_t 
         /* verification: drafted tokens are tested in order until the first rejection */
         int32_t a = 0;
         int near_accept = 0;
+        double min_gap = INFINITY;
         double lse_p = 0.0, lse_q = 0.0;
         for (; a < k; ++a) {
             const char* qrow = (const char*)draft + (size_t)(((int64_t)b * k + a) * V) * es;
@@ -482,7 +484,9 @@ int oracle_gsd_verify(const void* draft, const void* target, int dtype, int32_t 
             const double ratio = exp((widen(prow, dtype, x) / T - lse_p) - (widen(qrow, dtype, x) / T - lse_q));
             const double U = oracle_gsd_uniform(seed, (uint32_t)a, (uint32_t)b);
             const double big = ratio > U ? ratio : U;
-            if (fabs(ratio - U) <= 1e-5 * big) near_accept = 1;
+            const double gap = fabs(ratio - U) / big;
+            if (gap < min_gap) min_gap = gap;
+            if (gap <= accept_rel_tol) near_accept = 1;
             if (!(ratio > U)) break;
         }
         accept_len[b] = a;
@@ -506,14 +510,15 @@ int oracle_gsd_verify(const void* draft, const void* target, int dtype, int32_t 
             if (best < 0 || score > s1) {
                 best = i;
                 s1 = score;
-                const double wl = w - 4e-6 * (p + q);
+                const double wl = w - weight_rel_tol * (p + q);
                 floor1 = wl > 0.0 ? log(wl) + oracle_gumbel(words[i & 3]) : -INFINITY;
             }
         }
         next_token[b] = s1 > -INFINITY ? (int32_t)best : 0;
         if (info) {
-            /* how many other tokens could win if every weight moved by 4e-6 (p + q): the sensitivity of the
-             * residual to errors of the two normalisers */
+            /* how many other tokens could win if every weight moved by weight_rel_tol (p + q): the sensitivity of
+             * the residual to relative errors of the two normalisers, for whoever compares an implementation
+             * with inexact normalisers against this one */
             int32_t rivals = 0;
             for (int64_t i = 0; i < V; ++i) {
                 if ((i & 3) == 0) {
@@ -524,10 +529,11 @@ int oracle_gsd_verify(const void* draft, const void* target, int dtype, int32_t 
                 const double p = exp(widen(prow, dtype, i) / T - lse_p);
                 const double q = qrow ? exp(widen(qrow, dtype, i) / T - lse_q) : 0.0;
                 const double w = p - q > 0.0 ? p - q : 0.0;
-                const double top = log(w + 4e-6 * (p + q)) + oracle_gumbel(words[i & 3]);
+                const double top = log(w + weight_rel_tol * (p + q)) + oracle_gumbel(words[i & 3]);
                 if (top >= floor1) ++rivals;
             }
             info[b].near_accept = near_accept;
+            info[b].min_accept_gap = min_gap;
             info[b].rivals = rivals;
             info[b].lse_p = lse_p;
             info[b].lse_q = a < k ? lse_q : 0.0;

@@ -158,20 +158,25 @@ void oracle_arrival_tree_shape(const int32_t* parent, const int32_t* rank, int32
  *   max(P - Q, 0) / sum at position a, if a == k a draw from P at position k; both by an exponential race
  *   argmin e_i / weight_i with e from the counter (i >> 2, a, b, 1) (the appendix notes that GSD's draws can be
  *   made with races; any sampler would do).  A row whose weights are all zero gives token 0.
- * info[b] (may be NULL): near_accept = 1 iff some tested ratio was within 1e-5 (relative) of its uniform;
- * rivals = number of other tokens that could win the final race if every weight moved by 4e-6 (p + q), i.e. by
- * what single-precision normalisers can shift it; lse_p, lse_q: normalisers at the last tested position.
+ * The results above are exact in double precision and carry no tolerance.  info[b] (may be NULL) reports how
+ * sensitive they are, for a caller that compares an implementation with inexact normalisers against this one and
+ * says how inexact: min_accept_gap = smallest |ratio - U| / max(ratio, U) over the tested positions; near_accept =
+ * 1 iff that is <= accept_rel_tol; rivals = number of other tokens that could win the final race if every weight
+ * moved by weight_rel_tol (p + q); lse_p, lse_q: normalisers at the last tested position.  With both tolerances 0
+ * the flags report exact coincidences only.
  */
 typedef struct {
     int32_t near_accept;
     int32_t rivals;
     double lse_p, lse_q;
     double score; /* winning score ln(weight) - ln(e) of the final race */
+    double min_accept_gap;
 } oracle_gsd_info;
 
 int oracle_gsd_verify(const void* draft, const void* target, int dtype, int32_t B, int32_t k, int64_t V,
                       const int32_t* draft_tokens, float temperature, uint64_t seed,
-                      int32_t* accept_len, int32_t* next_token, oracle_gsd_info* info);
+                      int32_t* accept_len, int32_t* next_token, oracle_gsd_info* info, double accept_rel_tol,
+                      double weight_rel_tol);
 double oracle_logsumexp(const void* row, int dtype, int64_t V, float temperature);
 double oracle_gsd_uniform(uint64_t seed, uint32_t j, uint32_t b);
 

@@ -134,3 +134,15 @@ def test_sensitivity_flags(oracle_mod):
     assert o["info"]["lse_p"][0] == pytest.approx(np.log(7 + np.exp(6.0)), rel=1e-14)
     with pytest.raises(ValueError):
         oracle_mod.gsd_verify(draft, target, np.array([[V]], dtype=np.int32), 1.0, 1)
+    # the report follows the tolerances it is given and the results never do: P(5)/Q(5) against its uniform
+    gap = o["info"]["min_accept_gap"][0]
+    assert 0 < gap < 1
+    for tol, flag in ((0.0, 0), (gap * 0.99, 0), (gap * 1.01, 1), (1.0, 1)):
+        o2 = oracle_mod.gsd_verify(draft, target, np.array([[5]], dtype=np.int32), 1.0, 1, want_info=True,
+                                   accept_rel_tol=tol, weight_rel_tol=tol)
+        assert o2["info"]["near_accept"][0] == flag
+        assert o2["accept_len"][0] == o["accept_len"][0] and o2["next_token"][0] == o["next_token"][0]
+    # with weights allowed to move by their own size every other token with positive mass is a rival
+    o3 = oracle_mod.gsd_verify(draft, target, np.array([[5]], dtype=np.int32), 1.0, 1, want_info=True,
+                               weight_rel_tol=1.0)
+    assert o3["info"]["rivals"][0] >= 1
