@@ -83,9 +83,10 @@ def measure_verify(w, sets, args, dev, timed_baseline):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / n
 
-    rough = batch(n_ev)  # this measurement's own warm-up (the wall-clock loop above may have been short)
+    rough = batch(n_ev)
     n_ev = max(n_ev, min(400, int(20.0 / rough)))  # about 20 ms of launches, so that a short kernel is not timed on 2 ms
-    kernel_ms = batch(n_ev)
+    batch(n_ev)  # this measurement's own warm-up: the wall-clock loop above may have been short, and the device idles
+    kernel_ms = batch(n_ev)  # (and clocks down) whenever the host is busy with the oracle
     pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(min(n_ev, 64))]
     for i, (a0, a1) in enumerate(pairs):
         a0.record()
@@ -130,11 +131,16 @@ def measure_verify(w, sets, args, dev, timed_baseline):
                                       "race_kernel_vs_plain_read": round(probe_ms / kernel_ms, 4)},
         },
     }
-    base_out, check = oracle_side(w, sets[0], calls[0], variant, timed_baseline)
-    out["check"] = check
-    if base_out is not None:
-        out["cpu_baseline"] = base_out
+    out["_oracle"] = lambda: oracle_side(w, sets[0], calls[0], variant, timed_baseline)
     return out
+
+
+def add_oracle_side(rec):
+    """The host-side part of one workload's record, run after every GPU measurement of the run is done."""
+    base_out, check = rec.pop("_oracle")()
+    rec["check"] = check
+    if base_out is not None:
+        rec["cpu_baseline"] = base_out
 
 
 def main():
@@ -194,6 +200,8 @@ def main():
     torch.cuda.synchronize()
     head = measure_verify(w, inputs[args.workload], args, dev, timed_baseline=not args.no_cpu_baseline)
     per = [measure_verify(wl.WORKLOADS[i], inputs[i], args, dev, timed_baseline=False) for i in others]
+    for rec in [head] + per:
+        add_oracle_side(rec)
 
     out = {
         "metric": "race_elements_per_sec", "value": head["value"], "unit": "elements/s", "n_gpus": 1,
