@@ -341,15 +341,16 @@ int ersd_arrival_tree_validate_host(const int32_t* parent_host, const int32_t* r
  * experiments (Section 5): R(j_1 .. j_l) = r[j_1] * ... * r[j_l], r[j] = accept_by_rank[j] = probability that the
  * child holding arrival j of a context is accepted given that its parent was.  Greedy growth from a priority
  * queue, O(k log k).  All pointers are HOST arrays; no device work.
- *   accept_by_rank [nr]: values in [0, 1]; the tree is optimal when they do not increase with j (the algorithm
- *   offers sibling j + 1 only after sibling j was taken); nr = largest number of children of a vertex
+ *   accept_by_rank [nr]: values in [0, 1] that do not increase with j (a later arrival is accepted less often;
+ *   the algorithm offers sibling j + 1 only after sibling j was taken); nr = largest number of children of a vertex
  *   (<= ERSD_MAX_RANK for use with ersd_race_verify_arrival_tree).
- *   parent, rank [k] out: the k drafted vertices in the order they were taken (so parent[n] < n; -1 = the root),
- *   in the layout ersd_race_verify_arrival_tree takes.  Equal acceptance values are taken in the order they
- *   entered the queue.
+ *   parent, rank [k] out: the k vertices with the largest R, in the order they were taken (so parent[n] < n; -1 =
+ *   the root), in the layout ersd_race_verify_arrival_tree takes.  Equal acceptance values are taken by depth,
+ *   then by index tuple, so the result is a function of the arguments alone.
  *   node_accept [k] out or NULL: R of every vertex.  expected_accepted out or NULL: their sum, the expected
  *   number of accepted drafted tokens under the model.
- * Returns ERSD_OK, ERSD_ERR_NULL_POINTER, or ERSD_ERR_INVALID_ARG (nr < 1, k < 1, a value outside [0, 1]).
+ * Returns ERSD_OK, ERSD_ERR_NULL_POINTER, or ERSD_ERR_INVALID_ARG (nr < 1, k < 1, a value outside [0, 1] or larger
+ * than its predecessor).
  */
 int ersd_tree_build_optimal_host(const double* accept_by_rank, int32_t nr, int32_t k, int32_t* parent,
                                  int32_t* rank, double* node_accept, double* expected_accepted);

@@ -72,7 +72,7 @@ def test_library_tree_equals_oracle_tree():
         nr = int(rng.integers(1, 9))
         r = np.sort(rng.random(nr))[::-1] * rng.uniform(0.3, 1.0)
         if trial % 5 == 0:
-            r = np.round(r, 1)  # equal values: the queue order decides
+            r = np.round(r, 1)  # equal values: depth, then index tuple, decide
         k = int(rng.integers(1, 200))
         parent, rank, acc, total = race.tree_build_optimal(r, k)
         ref = tb.optimal_tree(tuple(r), k)
@@ -88,7 +88,7 @@ def test_library_tree_large_and_argument_errors():
     parent, rank, acc, total = race.tree_build_optimal([0.8, 0.1, 0.05], 8192)
     assert race.arrival_tree_validate_host(parent, rank)
     assert np.all(np.diff(acc) <= 0) and total == pytest.approx(acc.sum())
-    for bad in ([], [1.5], [float("nan")], [-0.1]):
+    for bad in ([], [1.5], [float("nan")], [-0.1], [0.3, 0.5]):   # the last: acceptance must not increase with the rank
         with pytest.raises(race.ErsdError):
             race.tree_build_optimal(bad, 4)
     with pytest.raises(race.ErsdError):
