@@ -75,6 +75,11 @@ def lib():
         L.oracle_gsd_verify.argtypes = [vp, vp, ctypes.c_int, i32, i32, i64, vp, f32, u64, vp, vp, vp, ctypes.c_double,
                                         ctypes.c_double]
         L.oracle_gsd_verify.restype = ctypes.c_int
+        L.oracle_gsd_verify_tree.argtypes = [vp, vp, ctypes.c_int, i32, i32, i64, vp, vp, i32, vp, f32, u64, vp, vp, vp,
+                                             vp, ctypes.c_double, ctypes.c_double]
+        L.oracle_gsd_verify_tree.restype = ctypes.c_int
+        L.oracle_gsd_uniform_ctr.argtypes = [u64, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32]
+        L.oracle_gsd_uniform_ctr.restype = ctypes.c_double
         L.oracle_logsumexp.argtypes = [vp, ctypes.c_int, i64, f32]
         L.oracle_logsumexp.restype = ctypes.c_double
         L.oracle_gsd_uniform.argtypes = [u64, u32, u32]
@@ -333,6 +338,39 @@ def gsd_verify(draft, target, draft_tokens, temperature, seed, want_info=False, 
     if rc != 0:
         raise ValueError("oracle_gsd_verify: invalid arguments")
     out = dict(accept_len=acc, next_token=nxt)
+    if want_info:
+        out["info"] = info
+    return out
+
+
+def gsd_uniform_ctr(seed, r, j, b):
+    return lib().oracle_gsd_uniform_ctr(int(seed), int(r), int(j), int(b))
+
+
+def gsd_verify_tree(draft, target, parent, rank, draft_tokens, temperature, seed, max_rank=8, want_info=False,
+                    accept_rel_tol=0.0, weight_rel_tol=0.0):
+    """GSD on a draft tree (Algorithm 4's verification): draft, target [B,N+1,V]; parent, rank int32 [N];
+    draft_tokens [B,N] -> dict(accept_len, accept_node, emitted [B,N+1])."""
+    d, dt = _host(draft)
+    t, dt2 = _host(target)
+    assert dt == dt2
+    B, C, V = d.shape
+    N = C - 1
+    assert t.shape == (B, C, V)
+    par = np.ascontiguousarray(np.asarray(parent, dtype=np.int32))
+    rk = np.ascontiguousarray(np.asarray(rank, dtype=np.int32))
+    tok = np.ascontiguousarray(np.asarray(draft_tokens, dtype=np.int32))
+    assert par.shape == (N,) and rk.shape == (N,) and tok.shape == (B, N)
+    acc = np.zeros(B, dtype=np.int32)
+    node = np.zeros(B, dtype=np.int32)
+    emitted = np.zeros((B, C), dtype=np.int32)
+    info = np.zeros(B, dtype=GSD_INFO_DTYPE) if want_info else None
+    rc = lib().oracle_gsd_verify_tree(_ptr(d), _ptr(t), dt, B, N, V, _ptr(par), _ptr(rk), int(max_rank), _ptr(tok),
+                                      float(temperature), int(seed), _ptr(acc), _ptr(node), _ptr(emitted),
+                                      _ptr(info) if want_info else None, float(accept_rel_tol), float(weight_rel_tol))
+    if rc != 0:
+        raise ValueError("oracle_gsd_verify_tree: invalid arguments")
+    out = dict(accept_len=acc, accept_node=node, emitted=emitted)
     if want_info:
         out["info"] = info
     return out

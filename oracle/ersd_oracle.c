@@ -443,13 +443,16 @@ double oracle_logsumexp(const void* row, int dtype, int64_t V, float temperature
 }
 
 /* the uniform of the acceptance test at (sequence b, position j): word 0 of the counter (0, j, b, 2) */
-double oracle_gsd_uniform(uint64_t seed, uint32_t j, uint32_t b) {
+/* the uniform of an acceptance test: word 0 of the counter (r, j, b, 2); r = 0 in the sequence form, the child's
+ * rank in the tree form */
+double oracle_gsd_uniform_ctr(uint64_t seed, uint32_t r, uint32_t j, uint32_t b) {
     const uint32_t key[2] = {(uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32)};
-    const uint32_t ctr[4] = {0u, j, b, 2u};
+    const uint32_t ctr[4] = {r, j, b, 2u};
     uint32_t w[4];
     oracle_philox4x32(g_rounds, ctr, key, w);
     return ((double)w[0] + 0.5) * (1.0 / 4294967296.0);
 }
+double oracle_gsd_uniform(uint64_t seed, uint32_t j, uint32_t b) { return oracle_gsd_uniform_ctr(seed, 0u, j, b); }
 
 int oracle_gsd_verify(const void* draft, const void* target, int dtype, int32_t B, int32_t k, int64_t V,
                       const int32_t* draft_tokens, float temperature, uint64_t seed,
@@ -541,4 +544,137 @@ int oracle_gsd_verify(const void* draft, const void* target, int dtype, int32_t 
         }
     }
     return 0;
+}
+
+/* ---------------------------------------------------------------------------------------------------------------
+ * GSD on a draft tree (Algorithm 4, verification part; recursive rejection over the children of a context).
+ * The drafted tokens are given (Algorithm 4 draws the children of a context from Q without replacement, which is
+ * what the first arrivals of a race under Q are; the caller supplies them).  Per prompt, from the root context:
+ *   P_target <- P(. | context), Q_draft <- Q(. | context)
+ *   for the valid children of the context in the order of their ranks (a child whose drafted token is -1, a missing
+ *   arrival, is passed over): accept the child if P_target(x) / Q_draft(x) > U, U from the counter
+ *   (rank, context, b, 2), and go on at the child's context with fresh distributions; else
+ *       P_target <- max(P_target - Q_draft, 0); P_target <- P_target / sum(P_target)
+ *       Q_draft(x) <- 0;                        Q_draft  <- Q_draft / sum(Q_draft)
+ *   when no child is accepted (or there is none) the step ends with a draw from P_target, made as an exponential
+ *   race argmin e_i / P_target(i) with e from the counter (i >> 2, context, b, 1).
+ * A distribution that becomes all zero stays all zero (then nothing more is accepted and the draw gives token 0).
+ * accept_len[b], accept_node[b] (-1: none), emitted[b][C]: the accepted drafted tokens, then the drawn token, then -1.
+ * info (may be NULL) as for oracle_gsd_verify, over all tested children and the final draw; the two tolerances only
+ * shape that report.  A chain with ranks 0 gives exactly oracle_gsd_verify.
+ */
+int oracle_gsd_verify_tree(const void* draft, const void* target, int dtype, int32_t B, int32_t N, int64_t V,
+                           const int32_t* parent, const int32_t* rank, int32_t max_rank, const int32_t* draft_tokens,
+                           float temperature, uint64_t seed, int32_t* accept_len, int32_t* accept_node,
+                           int32_t* emitted, oracle_gsd_info* info, double accept_rel_tol, double weight_rel_tol) {
+    if (bad_common(draft, target, dtype, V, temperature)) return -1;
+    if (B < 1 || N < 1 || max_rank < 1 || !parent || !rank || !draft_tokens || !accept_len || !accept_node || !emitted)
+        return -1;
+    for (int64_t t = 0; t < (int64_t)B * N; ++t)
+        if (draft_tokens[t] < -1 || draft_tokens[t] >= V) return -1;
+    const int32_t C = N + 1;
+    int32_t* valid = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
+    int32_t* need = (int32_t*)malloc(sizeof(int32_t) * (size_t)C);
+    if (!valid || !need) { free(valid); free(need); return -1; }
+    oracle_arrival_tree_shape(parent, rank, N, max_rank, valid, need);
+    const size_t es = elem_size(dtype);
+    const double T = (double)temperature;
+    const uint32_t key[2] = {(uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32)};
+    if (g_threads > 0) {
+#ifdef _OPENMP
+        omp_set_num_threads(g_threads);
+#endif
+    }
+    int failed = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t b = 0; b < B; ++b) {
+        double* P = (double*)malloc(sizeof(double) * (size_t)V);
+        double* Q = (double*)malloc(sizeof(double) * (size_t)V);
+        if (!P || !Q) { free(P); free(Q); failed = 1; continue; }
+        int32_t ctx = 0, len = 0, node = -1, near_accept = 0;
+        double min_gap = INFINITY, lse_p = 0.0, lse_q = 0.0;
+        int32_t* out = emitted + (int64_t)b * C;
+        for (int32_t c = 0; c < C; ++c) out[c] = -1;
+        for (;;) {
+            const char* prow = (const char*)target + (size_t)(((int64_t)b * C + ctx) * V) * es;
+            const char* qrow = (const char*)draft + (size_t)(((int64_t)b * C + ctx) * V) * es;
+            lse_p = oracle_logsumexp(prow, dtype, V, temperature);
+            for (int64_t i = 0; i < V; ++i) P[i] = exp(widen(prow, dtype, i) / T - lse_p);
+            int32_t accepted = -1;
+            if (need[ctx] > 0) {
+                lse_q = oracle_logsumexp(qrow, dtype, V, temperature);
+                for (int64_t i = 0; i < V; ++i) Q[i] = exp(widen(qrow, dtype, i) / T - lse_q);
+                for (int32_t r = 0; r < max_rank && accepted < 0; ++r) {
+                    int32_t child = -1; /* the valid child of this context that holds arrival r */
+                    for (int32_t n = 0; n < N; ++n)
+                        if (valid[n] && parent[n] + 1 == ctx && rank[n] == r) { child = n; break; }
+                    if (child < 0) continue;
+                    const int32_t x = draft_tokens[(int64_t)b * N + child];
+                    if (x < 0) continue;
+                    const double ratio = P[x] / Q[x]; /* Q[x] > 0 for a token that was drawn from Q */
+                    const double U = oracle_gsd_uniform_ctr(seed, (uint32_t)r, (uint32_t)ctx, (uint32_t)b);
+                    const double big = ratio > U ? ratio : U;
+                    const double gap = fabs(ratio - U) / big;
+                    if (gap < min_gap) min_gap = gap;
+                    if (gap <= accept_rel_tol) near_accept = 1;
+                    if (ratio > U) { accepted = child; break; }
+                    double sp = 0.0, sq = 0.0;
+                    for (int64_t i = 0; i < V; ++i) { P[i] = P[i] - Q[i] > 0.0 ? P[i] - Q[i] : 0.0; sp += P[i]; }
+                    if (sp > 0.0) for (int64_t i = 0; i < V; ++i) P[i] /= sp;
+                    Q[x] = 0.0;
+                    for (int64_t i = 0; i < V; ++i) sq += Q[i];
+                    if (sq > 0.0) for (int64_t i = 0; i < V; ++i) Q[i] /= sq;
+                }
+            }
+            if (accepted >= 0) {
+                out[len++] = draft_tokens[(int64_t)b * N + accepted];
+                node = accepted;
+                ctx = accepted + 1;
+                continue;
+            }
+            /* the draw from what is left of P at this context */
+            int64_t best = -1;
+            double s1 = -INFINITY, floor1 = -INFINITY;
+            uint32_t words[4] = {0, 0, 0, 0};
+            for (int64_t i = 0; i < V; ++i) {
+                if ((i & 3) == 0) {
+                    const uint32_t ctr[4] = {(uint32_t)(i >> 2), (uint32_t)ctx, (uint32_t)b, 1u};
+                    oracle_philox4x32(g_rounds, ctr, key, words);
+                }
+                const double score = log(P[i]) + oracle_gumbel(words[i & 3]);
+                if (best < 0 || score > s1) {
+                    best = i;
+                    s1 = score;
+                    const double wl = P[i] * (1.0 - weight_rel_tol);
+                    floor1 = wl > 0.0 ? log(wl) + oracle_gumbel(words[i & 3]) : -INFINITY;
+                }
+            }
+            out[len] = s1 > -INFINITY ? (int32_t)best : 0;
+            if (info) {
+                int32_t rivals = 0;
+                for (int64_t i = 0; i < V; ++i) {
+                    if ((i & 3) == 0) {
+                        const uint32_t ctr[4] = {(uint32_t)(i >> 2), (uint32_t)ctx, (uint32_t)b, 1u};
+                        oracle_philox4x32(g_rounds, ctr, key, words);
+                    }
+                    if (i == best) continue;
+                    if (log(P[i] * (1.0 + weight_rel_tol)) + oracle_gumbel(words[i & 3]) >= floor1) ++rivals;
+                }
+                info[b].near_accept = near_accept;
+                info[b].min_accept_gap = min_gap;
+                info[b].rivals = rivals;
+                info[b].lse_p = lse_p;
+                info[b].lse_q = lse_q;
+                info[b].score = s1;
+            }
+            break;
+        }
+        accept_len[b] = len;
+        accept_node[b] = node;
+        free(P);
+        free(Q);
+    }
+    free(valid);
+    free(need);
+    return failed ? -1 : 0;
 }

@@ -179,6 +179,28 @@ int oracle_gsd_verify(const void* draft, const void* target, int dtype, int32_t 
                       double weight_rel_tol);
 double oracle_logsumexp(const void* row, int dtype, int64_t V, float temperature);
 double oracle_gsd_uniform(uint64_t seed, uint32_t j, uint32_t b);
+double oracle_gsd_uniform_ctr(uint64_t seed, uint32_t r, uint32_t j, uint32_t b);
+
+/*
+ * GSD on a draft tree: the verification part of Algorithm 4 (Appendix A), recursive rejection over the children of
+ * a context.  Tree layout, contexts and node validity as in oracle_race_verify_arrival_tree; draft, target [B,N+1,V];
+ * draft_tokens [B,N]: what every node drafted (-1: nothing), given by the caller (Algorithm 4 draws the children of
+ * a context from Q without replacement, i.e. the first arrivals of a race under Q).
+ *   At a context: P_target = P, Q_draft = Q; its valid children are tested in the order of their ranks; child with
+ *   token x is accepted iff P_target(x) / Q_draft(x) > U, U = (w + 1/2) 2^-32 with w = word 0 of the counter
+ *   (rank, context, b, 2), and the walk goes on at the child's context with fresh distributions; on a rejection
+ *   P_target <- max(P_target - Q_draft, 0) normalised, Q_draft(x) <- 0 and normalised.  When no child is accepted
+ *   the step ends with a draw from P_target by the race argmin e_i / P_target(i), e from (i >> 2, context, b, 1).
+ *   A distribution that becomes all zero stays so (no further acceptance; the draw gives token 0).
+ * accept_len [B], accept_node [B] (-1: none), emitted [B,N+1]: accepted drafted tokens, the drawn token, then -1.
+ * info, accept_rel_tol, weight_rel_tol: the sensitivity report of oracle_gsd_verify (rivals here: other tokens that
+ * could win the draw if every weight moved by weight_rel_tol of itself).  A chain with ranks 0 equals
+ * oracle_gsd_verify on the same rows.
+ */
+int oracle_gsd_verify_tree(const void* draft, const void* target, int dtype, int32_t B, int32_t N, int64_t V,
+                           const int32_t* parent, const int32_t* rank, int32_t max_rank, const int32_t* draft_tokens,
+                           float temperature, uint64_t seed, int32_t* accept_len, int32_t* accept_node,
+                           int32_t* emitted, oracle_gsd_info* info, double accept_rel_tol, double weight_rel_tol);
 
 /* Threads the row loops will use (OpenMP), for reporting. */
 int oracle_num_threads(void);
