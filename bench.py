@@ -183,6 +183,8 @@ def main():
     from paper_2504_15475_amd import race, workloads as wl
     race.lib()
     if args.workload == 5:
+        if args.entry == "gsd":
+            return bench_gsd_tree(args, wl.ARRIVAL_TREE, dev)
         return bench_arrival_tree(args, wl.ARRIVAL_TREE, dev)
     w = wl.WORKLOADS[args.workload]
     if args.entry == "sample":
@@ -308,6 +310,55 @@ def bench_arrival_tree(args, w, dev):
                                 "kind": "oracle", "sample": f"first {nb} of {B} prompts, one pass",
                                 "check": {"mismatches_vs_oracle": mism}}
     print(json.dumps(line), flush=True)
+    return 0
+
+
+def bench_gsd_tree(args, w, dev):
+    """The comparison method on the draft tree of workload 5 (ersd_gsd_verify_tree, Algorithm 4's verification) on the
+    logits and drafted tokens of the arrival-tree verification; events bracket the call (one kernel)."""
+    from paper_2504_15475_amd import race, workloads as wl
+    base = wl.make_inputs(w, dev)
+    sets = [base]
+    for _ in range(max(1, args.buffers) - 1):
+        sets.append(dict(base, draft=(base["draft"].float() + 0.01 * torch.randn(base["draft"].shape, device=dev))
+                         .to(w.dtype).contiguous(),
+                         target=(base["target"].float() + 0.01 * torch.randn(base["target"].shape, device=dev))
+                         .to(w.dtype).contiguous()))
+    plan = race.arrival_tree_prepare(base["parent"], base["rank"])
+    for x in sets:  # the drafting stage is not part of verification
+        x["tokens"] = race.race_verify_arrival_tree(x["draft"], x["target"], x["parent"], x["rank"], w.temperature,
+                                                    w.seed, plan=plan)[0]
+    B, C, V = base["draft"].shape
+
+    def step(i):
+        x = sets[i % len(sets)]
+        return race.gsd_verify_tree(x["draft"], x["target"], x["parent"], x["rank"], x["tokens"], w.temperature, w.seed,
+                                    plan=plan)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    K = args.steps
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(K):
+        out = step(i)
+    e1.record()
+    torch.cuda.synchronize()
+    total_s = time.perf_counter() - t0
+    gpu_ms = e0.elapsed_time(e1) / K
+    print(json.dumps({
+        "metric": "verification_steps_per_sec", "value": K / total_s, "unit": "steps/s", "n_gpus": 1,
+        "steps": K, "warmup": args.warmup, "ms_per_step": total_s * 1e3 / K, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 exponentials, f64 sums and residual recursion", "data": "synthetic",
+        "config": {"workload": w.name, "entry": "ersd_gsd_verify_tree (comparison method, Algorithm 4's verification)",
+                   "B": B, "contexts": C, "V": V, "mean_accept_len": float(out[0].float().mean())},
+        "latency": {"ms_per_call_gpu_events": round(gpu_ms, 5),
+                    "note": "one workgroup per prompt walks its tree; the rows read depend on the walk"},
+        "roofline": None,
+    }), flush=True)
     return 0
 
 

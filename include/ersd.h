@@ -180,6 +180,31 @@ int ersd_race_stage_accept(int variant, ersd_dtype dt, int32_t B, int32_t m, int
                            const void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The comparison method on a draft tree: the verification part of Algorithm 4 (Appendix A), recursive rejection over
+ * the children of a context, on the layout of ersd_race_verify_arrival_tree (contexts, parent, rank, node validity).
+ *   draft_logits, target_logits [B, N + 1, V] (one row per context); draft_tokens [B, N]: what every node drafted
+ *   (-1: nothing), e.g. the draft_tokens output of ersd_race_verify_arrival_tree (Algorithm 4 draws the children of
+ *   a context from Q without replacement, which the first arrivals of a race under Q are).
+ *   plan: the tree's prepared shape (ersd_arrival_tree_prepare on the same parent, rank).
+ *   Walk per prompt, from the root context: P_target = P, Q_draft = Q at the context; its valid children are tested
+ *   in the order of their ranks: child with token x is accepted iff P_target(x) / Q_draft(x) > U, U = (w + 1/2) 2^-32,
+ *   w = word 0 of the Philox counter (rank, context, b, 2), and the walk goes on at the child's context; on a
+ *   rejection P_target <- max(P_target - Q_draft, 0) normalised and x leaves Q_draft (normalised again).  When no
+ *   child is accepted the step ends with a draw from P_target, made as the race argmin e_i / P_target(i) with e from
+ *   the counter (i >> 2, context, b, 1).  A chain with ranks 0 is exactly ersd_gsd_verify.
+ *   accept_len [B], accept_node [B] (-1: none), emitted [B, N + 1] out: accepted drafted tokens, the drawn token,
+ *   then -1.
+ * Precision as for ersd_gsd_verify: probabilities from single-precision exponentials, sums and the residual recursion
+ * in double precision; a test whose ratio lies within about 1e-6 (relative) of its uniform, or a draw whose two best
+ * scores are as close as the weights' error, may resolve differently from an evaluation in double precision.
+ * No workspace; one workgroup per prompt walks its tree; enqueues on `stream`.
+ */
+int ersd_gsd_verify_tree(const void* draft_logits, const void* target_logits, ersd_dtype dt, int32_t B, int32_t N,
+                         int32_t V, const int32_t* parent, const int32_t* rank, const void* plan, size_t plan_bytes,
+                         const int32_t* draft_tokens, float temperature, uint64_t seed,
+                         int32_t* accept_len, int32_t* accept_node, int32_t* emitted, void* stream);
+
+/*
  * Host-only description of how a job is cut into shares of equal cost for `blocks` workgroups (1..4096): every
  * row is a run of 8-token groups, rows are laid end to end, and share b covers the global group indices
  * [block_start[b], block_start[b+1]).  The cost of a share is 10 per group of a row pair, 5 per group of a

@@ -7,6 +7,7 @@ ROOT = os.path.dirname(HERE)
 SRC = os.path.join(HERE, "csrc", "ersd_race.hip")
 SRC_HOST = os.path.join(HERE, "csrc", "ersd_tree.cpp")  # host-only part of the library
 SRC_GSD = os.path.join(HERE, "csrc", "ersd_gsd.hip")    # the comparison method
+SRC_GSD_TREE = os.path.join(HERE, "csrc", "ersd_gsd_tree.hip")  # the comparison method on a draft tree
 LIB = os.path.join(HERE, "libersd.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
@@ -24,7 +25,7 @@ def build(extra=()):
     rounds = os.environ.get("ERSD_PHILOX_ROUNDS")  # 7 by default (set in the source); 10 = the generator's standard
     if rounds:
         extra = (*extra, f"-DERSD_PHILOX_ROUNDS={int(rounds)}")
-    cmd = [HIPCC, *FLAGS, *extra, "-o", LIB, SRC, SRC_GSD, SRC_HOST]
+    cmd = [HIPCC, *FLAGS, *extra, "-o", LIB, SRC, SRC_GSD, SRC_GSD_TREE, SRC_HOST]
     subprocess.run(cmd, check=True)
     return LIB
 

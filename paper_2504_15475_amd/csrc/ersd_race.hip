@@ -39,6 +39,7 @@
 #include "ersd.h"
 #include "ersd_partition.h"
 #include "ersd_philox.h"
+#include "ersd_tree_plan.h"
 
 namespace {
 
@@ -1814,7 +1815,9 @@ struct ArrLayout {
     size_t out, outq, arrivals, valid, need, wprefix, total;
 };
 
-size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
+using ersd_plan::align16;
+using ersd_plan::PlanLayout;
+using ersd_plan::plan_layout;
 
 ArrLayout arrival_layout(int32_t B, int32_t N, int32_t V) {
     const int32_t C = N + 1;
@@ -1828,19 +1831,6 @@ ArrLayout arrival_layout(int32_t B, int32_t N, int32_t V) {
     l.need = align16(l.valid + (size_t)N * sizeof(int32_t));
     l.wprefix = align16(l.need + (size_t)C * sizeof(int32_t));
     l.total = align16(l.wprefix + (size_t)(C + 1) * sizeof(uint32_t));
-    return l;
-}
-
-// A prepared tree shape (ersd_arrival_tree_prepare): valid[N], need[N + 1], wprefix[N + 2], each 16-byte aligned.
-struct PlanLayout {
-    size_t valid, need, wprefix, total;
-};
-PlanLayout plan_layout(int32_t N) {
-    PlanLayout l;
-    l.valid = 0;
-    l.need = align16(l.valid + (size_t)N * sizeof(int32_t));
-    l.wprefix = align16(l.need + (size_t)(N + 1) * sizeof(int32_t));
-    l.total = align16(l.wprefix + (size_t)(N + 2) * sizeof(uint32_t));
     return l;
 }
 

@@ -487,6 +487,37 @@ def arrival_plan_describe(B, N, V, need, blocks):
     return dict(G=G.value, nslot=nslot.value, block_start=start[: G.value + 1], row_first=first, row_last=last)
 
 
+def gsd_verify_tree(draft_logits, target_logits, parent, rank, draft_tokens, temperature, seed, plan=None):
+    """GSD on a draft tree (Algorithm 4's verification).  draft, target [B,N+1,V]; parent, rank int32 [N];
+    draft_tokens int32 [B,N] (e.g. from race_verify_arrival_tree) -> (accept_len [B], accept_node [B], emitted [B,N+1])."""
+    d, t = _dev(draft_logits, "draft_logits"), _dev(target_logits, "target_logits")
+    par, rk, tok = _dev(parent, "parent"), _dev(rank, "rank"), _dev(draft_tokens, "draft_tokens")
+    if not (d.is_contiguous() and t.is_contiguous() and tok.is_contiguous()):
+        raise ValueError("logits and tokens must be contiguous")
+    code = _dtype_code(d)
+    if _dtype_code(t) != code:
+        raise TypeError("draft and target logits must share a dtype")
+    B, C, V = d.shape
+    N = C - 1
+    if tuple(t.shape) != (B, C, V) or tuple(tok.shape) != (B, N) or tok.dtype != torch.int32:
+        raise ValueError("target_logits must be [B,N+1,V] and draft_tokens int32 [B,N]")
+    if par.dtype != torch.int32 or rk.dtype != torch.int32 or tuple(par.shape) != (N,) or tuple(rk.shape) != (N,):
+        raise ValueError("parent and rank must be int32 [N]")
+    if plan is None:
+        plan = arrival_tree_prepare(par, rk)
+    i32 = dict(dtype=torch.int32, device=d.device)
+    acc, node, emitted = torch.empty((B,), **i32), torch.empty((B,), **i32), torch.empty((B, C), **i32)
+    L = lib()
+    vp, ci, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    L.ersd_gsd_verify_tree.argtypes = [vp, vp, ctypes.c_int, ci, ci, ci, vp, vp, vp, sz, vp, ctypes.c_float,
+                                       ctypes.c_uint64, vp, vp, vp, vp]
+    _check(L.ersd_gsd_verify_tree(d.data_ptr(), t.data_ptr(), code, B, N, V, par.data_ptr(), rk.data_ptr(),
+                                  plan.data_ptr(), plan.numel() * plan.element_size(), tok.data_ptr(),
+                                  float(temperature), int(seed), acc.data_ptr(), node.data_ptr(), emitted.data_ptr(),
+                                  _stream()))
+    return acc, node, emitted
+
+
 class _TestHooks(ctypes.Structure):
     _fields_ = [("force_blocks", ctypes.c_int32), ("exhaustive", ctypes.c_int32), ("seg_cost_units", ctypes.c_int32)]
 

@@ -307,3 +307,20 @@ def test_prepared_arrival_tree_entry_points_check_their_arguments_on_the_host(L)
 
     assert call(d=None) == -1 and call(plan=None) == -1 and call(plan=FAKE + 4) == -4 and call(T=-1.0) == -2
     assert call(N=0) == -2 and call(stride=999) == -2 and call(pb=need - 16) == -5 and call(wsb=64) == -5
+
+
+def test_gsd_tree_entry_point_checks_its_arguments_on_the_host(L):
+    import ctypes
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    L.ersd_arrival_tree_plan_bytes.argtypes = [i32]
+    L.ersd_arrival_tree_plan_bytes.restype = sz
+    need = L.ersd_arrival_tree_plan_bytes(10)
+    L.ersd_gsd_verify_tree.argtypes = [vp, vp, ctypes.c_int, i32, i32, i32, vp, vp, vp, sz, vp, ctypes.c_float,
+                                       ctypes.c_uint64, vp, vp, vp, vp]
+
+    def call(d=FAKE, dt=0, B=2, N=10, V=1000, plan=FAKE, pb=need, tok=FAKE, T=1.0, o=FAKE):
+        return L.ersd_gsd_verify_tree(d, FAKE, dt, B, N, V, FAKE, FAKE, plan, pb, tok, T, 0, o, FAKE, FAKE, None)
+
+    assert call(d=None) == -1 and call(plan=None) == -1 and call(tok=None) == -1 and call(o=None) == -1
+    assert call(dt=4) == -3 and call(T=float("inf")) == -2 and call(B=0) == -2 and call(N=0) == -2 and call(N=8193) == -2
+    assert call(d=FAKE + 2) == -4 and call(plan=FAKE + 8) == -4 and call(pb=need - 16) == -5

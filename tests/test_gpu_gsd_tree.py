@@ -1,0 +1,137 @@
+"""GPU parity of GSD on a draft tree (ersd_gsd_verify_tree, Algorithm 4's verification) against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+# What the library's single-precision probabilities can move (see tests/test_gpu_gsd.py for the derivation of the
+# first figure).  A weight of the draw is a residual several levels deep; its error relative to itself is not bounded
+# where P and Q nearly cancel, but such weights are tiny and do not win draws: 1e-4 of the weight itself is the
+# report's yardstick here, and the sequences it flags are not compared.
+ACCEPT_REL_TOL = 1e-5
+WEIGHT_REL_TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def race():
+    assert torch.cuda.is_available(), "GPU tests need the MI355X"
+    from paper_2504_15475_amd import race as r
+    r.lib()
+    r.set_test_hooks()
+    return r
+
+
+def random_tree(rng, N, max_children=3):
+    parent = np.full(N, -1, dtype=np.int32)
+    rank = np.zeros(N, dtype=np.int32)
+    count = {}
+    for n in range(N):
+        while True:
+            p = int(rng.integers(-1, n)) if n else -1
+            if count.get(p, 0) < max_children:
+                break
+        parent[n], rank[n] = p, count.get(p, 0)
+        count[p] = count.get(p, 0) + 1
+    return parent, rank
+
+
+def inputs(B, C, V, dtype, seed, noise):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    target = 3.0 * torch.randn((B, C, V), generator=g, device="cuda")
+    draft = target + noise * torch.randn((B, C, V), generator=g, device="cuda")
+    return draft.to(dtype).contiguous(), target.to(dtype).contiguous()
+
+
+def check(race, oracle_mod, draft, target, parent, rank, T, seed, note=""):
+    B, C, V = draft.shape
+    print(f"[case] gsd tree B={B} N={C - 1} V={V} {draft.dtype} T={T} seed={seed} {note}", flush=True)
+    par_d = torch.as_tensor(parent).cuda()
+    rk_d = torch.as_tensor(rank).cuda()
+    tok = race.race_verify_arrival_tree(draft, target, par_d, rk_d, T, seed)[0]      # the drafting stage
+    acc, node, emitted = (x.cpu().numpy() for x in race.gsd_verify_tree(draft, target, par_d, rk_d, tok, T, seed))
+    torch.cuda.synchronize()
+    o = oracle_mod.gsd_verify_tree(draft.cpu(), target.cpu(), parent, rank, tok.cpu().numpy(), T, seed,
+                                   max_rank=race.max_rank(), want_info=True, accept_rel_tol=ACCEPT_REL_TOL,
+                                   weight_rel_tol=WEIGHT_REL_TOL)
+    skipped = loose = 0
+    for b in range(B):
+        if o["info"]["near_accept"][b]:
+            skipped += 1
+            continue
+        assert acc[b] == o["accept_len"][b] and node[b] == o["accept_node"][b], (
+            f"prompt {b}: accepted {acc[b]} (node {node[b]}) != {o['accept_len'][b]} (node {o['accept_node'][b]})")
+        a = int(acc[b])
+        assert emitted[b, :a].tolist() == o["emitted"][b, :a].tolist() and (emitted[b, a + 1:] == -1).all()
+        if o["info"]["rivals"][b] > 0:
+            loose += 1
+            continue
+        assert emitted[b, a] == o["emitted"][b, a], f"prompt {b}: drawn token {emitted[b, a]} != {o['emitted'][b, a]}"
+    print(f"[case] ok: skipped {skipped}, draws with rivals {loose}, mean accepted {o['accept_len'].mean():.2f}", flush=True)
+    assert skipped + loose <= max(2, B // 20)
+    return o
+
+
+@pytest.mark.parametrize("shape", [(6, 7, 1000, torch.float32), (5, 12, 4099, torch.bfloat16), (4, 9, 40960, torch.bfloat16),
+                                   (3, 5, 70001, torch.float32), (40, 6, 8, torch.float32), (2, 10, 131072, torch.bfloat16)],
+                         ids=lambda s: f"B{s[0]}-N{s[1]}-V{s[2]}-{str(s[3])[6:]}")
+@pytest.mark.parametrize("T", [1.0, 0.7])
+def test_random_trees_match_oracle(race, oracle_mod, shape, T):
+    B, N, V, dtype = shape
+    rng = np.random.default_rng(N * 7 + V)
+    parent, rank = random_tree(rng, N)
+    draft, target = inputs(B, N + 1, V, dtype, 41, noise=0.8)
+    o = check(race, oracle_mod, draft, target, parent, rank, T, 9)
+    assert V <= 8 or 0 < o["accept_len"].mean()
+
+
+def test_chain_equals_the_sequence_call_and_malformed_nodes_are_passed_over(race, oracle_mod):
+    B, k, V = 7, 5, 20008
+    draft, target = inputs(B, k + 1, V, torch.bfloat16, 5, noise=0.6)
+    chain_p = torch.arange(-1, k - 1, dtype=torch.int32, device="cuda")
+    chain_r = torch.zeros(k, dtype=torch.int32, device="cuda")
+    tok = race.race_verify_arrival_tree(draft, target, chain_p, chain_r, 1.0, 3)[0]
+    acc_t, node_t, em_t = race.gsd_verify_tree(draft, target, chain_p, chain_r, tok, 1.0, 3)
+    acc_s, nxt_s = race.gsd_verify(draft[:, :k].contiguous(), target, tok, 1.0, 3)
+    assert torch.equal(acc_t, acc_s)
+    for b in range(B):
+        a = int(acc_s[b])
+        assert int(em_t[b, a]) == int(nxt_s[b]) and int(node_t[b]) == a - 1
+    # malformed entries (parent >= node, rank out of range, duplicate rank) draft nothing and are never tested
+    parent = np.array([-1, -1, 0, 5, 0, 1, 1], dtype=np.int32)
+    rank = np.array([0, 1, 0, 0, 0, 9, 0], dtype=np.int32)
+    d2, t2 = inputs(4, 8, 6152, torch.float32, 6, noise=0.7)
+    check(race, oracle_mod, d2, t2, parent, rank, 1.0, 8, note="malformed")
+
+
+def test_identical_models_accept_the_first_child_everywhere(race, oracle_mod):
+    B, V = 5, 9000
+    x, _ = inputs(B, 6, V, torch.float32, 7, noise=0.0)
+    parent = np.array([-1, -1, 0, 0, 2], dtype=np.int32)
+    rank = np.array([0, 1, 0, 1, 0], dtype=np.int32)
+    par_d, rk_d = torch.as_tensor(parent).cuda(), torch.as_tensor(rank).cuda()
+    tok = race.race_verify_arrival_tree(x, x, par_d, rk_d, 1.0, 2)[0]
+    acc, node, emitted = race.gsd_verify_tree(x, x, par_d, rk_d, tok, 1.0, 2)
+    assert (acc == 3).all() and (node == 4).all()
+    check(race, oracle_mod, x, x, parent, rank, 1.0, 2, note="P == Q")
+
+
+def test_full_size_tree_matches_oracle_on_a_sample(race, oracle_mod):
+    from paper_2504_15475_amd import workloads as wl
+    w = wl.ARRIVAL_TREE
+    x = wl.make_inputs(w, "cuda")
+    tok = race.race_verify_arrival_tree(x["draft"], x["target"], x["parent"], x["rank"], w.temperature, w.seed)[0]
+    acc, node, emitted = race.gsd_verify_tree(x["draft"], x["target"], x["parent"], x["rank"], tok, w.temperature, w.seed)
+    torch.cuda.synchronize()
+    nb = 3   # the oracle takes a few seconds per prompt at this size
+    o = oracle_mod.gsd_verify_tree(x["draft"][:nb].cpu(), x["target"][:nb].cpu(), x["parent"].cpu().numpy(),
+                                   x["rank"].cpu().numpy(), tok[:nb].cpu().numpy(), w.temperature, w.seed,
+                                   max_rank=race.max_rank(), want_info=True, accept_rel_tol=ACCEPT_REL_TOL,
+                                   weight_rel_tol=WEIGHT_REL_TOL)
+    for b in range(nb):
+        if o["info"]["near_accept"][b]:
+            continue
+        assert int(acc[b]) == o["accept_len"][b] and int(node[b]) == o["accept_node"][b]
+        if o["info"]["rivals"][b] == 0:
+            assert emitted[b].cpu().numpy().tolist() == o["emitted"][b].tolist()
