@@ -583,30 +583,41 @@ __device__ void filter_stream(const RaceArgs& a, const Seg& c, Lds& lds) {
     const Raw& pa = pr[0];
     const Raw& qa = q[0];
 
-    // Bootstrap: each wavefront starts from a lower bound of the maximum taken from the first two tokens of every
-    // lane's first group (no barrier: the workgroup's bound in LDS is merged in at every tile).
+    // Bootstrap: each wavefront starts from a lower bound of the maximum: every lane scores, per side, the token
+    // with the largest logit among the 8 it holds of the first tile (one logarithm per lane and side), and the
+    // wavefront takes the best.  The better this start, the fewer group bounds reach tau while it is still rising.
+    // (No barrier: the workgroup's bound in LDS is read at every tile.)
     {
-        uint32_t w[4];
-        philox4x32((uint32_t)first >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, w);
-        float taup = kTauInit, tauq = kTauInit;
-        float bq[2] = {kTauInit, kTauInit};
+        const int32_t i0 = first, i1 = RAWF32 ? TS::piece_b(c.begin, tid) : first + 4;
+        uint32_t x[8];
+        philox4x32((uint32_t)i0 >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, x);
+        philox4x32((uint32_t)i1 >> 2, c.c1, c.c2, c.c3, a.key0, a.key1, x + 4);
+        float blp = -INFINITY, blq = -INFINITY;  // the lane's largest logit per side, and that token's word
+        uint32_t bxp = 0, bxq = 0;
 #pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            if (first + e < c.end) {
-                const float l2e = log2_exponential(w[e]);
-                const float sp = fmaf(raw_logit<RAWF32>(pa, e), c2, -l2e);
-                if (sp > -INFINITY) taup = fmaxf(taup, sp - refine_err(sp));
-                if (HASQ) {
-                    const float sq = fmaf(raw_logit<RAWF32>(qa, e), c2, -l2e);
-                    if (sq > -INFINITY) bq[e] = fmaxf(kTauInit, sq - refine_err(sq));
-                }
+        for (int e = 0; e < 8; ++e) {
+            const int32_t idx = e < 4 ? i0 + e : i1 + e - 4;
+            const bool in = idx < c.end;
+            const float lp = raw_logit_const<RAWF32>(pa, e);
+            if (in && lp > blp) { blp = lp; bxp = x[e]; }
+            if (HASQ) {
+                const float lq = raw_logit_const<RAWF32>(qa, e);
+                if (in && lq > blq) { blq = lq; bxq = x[e]; }
             }
         }
+        float taup = kTauInit, tauq = kTauInit;
+        const float sp = fmaf(blp, c2, -log2_exponential(bxp));
+        if (sp > -INFINITY) taup = sp - refine_err(sp);
         taup = wave_max(taup);
-        // draft side: the largest bound, or (arrival trees) the nq-th largest of this wavefront's sample, which is
-        // below the nq-th largest score of the segment.  These tokens are not entered into lds.top: the stream
-        // meets them again.
-        if (HASQ) tauq = ARR && c.nq > 1 ? wave_nth_largest(bq[0], bq[1], c.nq) : wave_max(fmaxf(bq[0], bq[1]));
+        if (HASQ) {
+            const float sq = fmaf(blq, c2, -log2_exponential(bxq));
+            float bq = kTauInit;
+            if (sq > -INFINITY) bq = fmaxf(kTauInit, sq - refine_err(sq));
+            // draft side: the largest bound, or (arrival trees) the nq-th largest of the wavefront's 64 tokens, which
+            // is below the nq-th largest score of the segment.  These tokens are not entered into lds.top: the stream
+            // meets them again.
+            tauq = ARR && c.nq > 1 ? wave_nth_largest(bq, kTauInit, c.nq) : wave_max(bq);
+        }
         if ((tid & (kWave - 1)) == 0) {
             lds_tau_raise(lds, 1, taup);
             if (HASQ) lds_tau_raise(lds, 0, tauq);
