@@ -239,6 +239,7 @@ typedef struct {
     int32_t force_blocks;      /* > 0: workgroups the race kernels are launched with (default 0: as many as are resident) */
     int32_t exhaustive;        /* != 0: every token is scored in double precision inside the race kernels (default 0) */
     int32_t seg_cost_units;    /* >= 0: cost charged to every row start when the job is cut up (default -1) */
+    int32_t align_groups;      /* >= 0: 8-token groups a share's start is aligned to, a power of two; 0 or 1: none (default -1) */
 } ersd_test_hooks;
 void ersd_test_hooks_set(const ersd_test_hooks* hooks);
 

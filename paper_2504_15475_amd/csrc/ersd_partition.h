@@ -28,6 +28,7 @@ struct Part {
     uint64_t Us;          // cost units per sequence
     uint64_t pair_units;  // cost units of the pair rows of one sequence
     uint32_t S;           // cost units charged to every row start (0 with a weight table)
+    uint32_t amask;       // shares start at groups that are multiples of amask + 1 (a power of two): whole cache lines
     uint32_t Lp, Ls;      // cost units of a whole pair row / target-only row: S + weight * V8
     uint64_t rows;        // target rows = races
     uint32_t V8;          // groups per row
@@ -97,6 +98,7 @@ __host__ __device__ inline PartPos part_unit_to_pos(const Part& p, uint64_t u) {
             const uint32_t off = r2 - jj * p.Ls;
             o.grp = off < p.S ? 0 : (off - p.S) / kWSingle;
         }
+        o.grp &= ~p.amask;
         o.row = (uint64_t)seq * p.kt + o.j;
         return o;
     }
@@ -116,7 +118,7 @@ __host__ __device__ inline PartPos part_unit_to_pos(const Part& p, uint64_t u) {
     }
     o.seq = seq;
     o.j = (uint32_t)row;
-    o.grp = (uint32_t)grp;
+    o.grp = (uint32_t)grp & ~p.amask;
     o.row = seq * p.kt + row;
     return o;
 }
@@ -148,12 +150,13 @@ __host__ __device__ inline uint32_t part_block_of_unit(const Part& p, uint64_t x
     }
     return (uint32_t)(((x + 1) * p.G - 1) / p.U);
 }
-// workgroup that holds the first group of row (seq, j): a share starts at the group that contains its first unit,
-// so a group belongs to the last share that starts at or before the group's last unit
+// workgroup that holds the first group of row (seq, j): a share starts at the aligned run of groups that contains
+// its first unit, so a group belongs to the last share that starts at or before the last unit of the group's run
 __host__ __device__ inline uint32_t part_first_block(const Part& p, uint64_t seq, uint32_t j) {
     uint32_t w;
     const uint64_t u0 = part_row_unit(p, seq, j, &w);
-    return part_block_of_unit(p, u0 + w - 1);
+    const uint32_t run = p.amask + 1 < p.V8 ? p.amask + 1 : p.V8;  // groups of the row's first run
+    return part_block_of_unit(p, u0 + (uint64_t)run * w - 1);
 }
 // workgroup that holds the last group of row (seq, j)
 __host__ __device__ inline uint32_t part_last_block(const Part& p, uint64_t seq, uint32_t j) {

@@ -519,12 +519,13 @@ def gsd_verify_tree(draft_logits, target_logits, parent, rank, draft_tokens, tem
 
 
 class _TestHooks(ctypes.Structure):
-    _fields_ = [("force_blocks", ctypes.c_int32), ("exhaustive", ctypes.c_int32), ("seg_cost_units", ctypes.c_int32)]
+    _fields_ = [("force_blocks", ctypes.c_int32), ("exhaustive", ctypes.c_int32), ("seg_cost_units", ctypes.c_int32),
+                ("align_groups", ctypes.c_int32)]
 
 
-def set_test_hooks(force_blocks=0, exhaustive=False, seg_cost_units=-1):
+def set_test_hooks(force_blocks=0, exhaustive=False, seg_cost_units=-1, align_groups=-1):
     """Test and tuning hooks of the library (process-wide; no arguments = all defaults)."""
-    h = _TestHooks(int(force_blocks), int(bool(exhaustive)), int(seg_cost_units))
+    h = _TestHooks(int(force_blocks), int(bool(exhaustive)), int(seg_cost_units), int(align_groups))
     lib().ersd_test_hooks_set(ctypes.byref(h))
 
 

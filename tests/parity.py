@@ -9,7 +9,7 @@ import numpy as np
 class _Hooks:
     """The library's test hooks as one piece of state: set() changes the named fields and applies all of them."""
 
-    DEFAULTS = dict(force_blocks=0, exhaustive=False, seg_cost_units=-1)
+    DEFAULTS = dict(force_blocks=0, exhaustive=False, seg_cost_units=-1, align_groups=-1)
 
     def __init__(self):
         self.kw = dict(self.DEFAULTS)
