@@ -56,3 +56,31 @@ def test_noalloc_refuses_a_job_beyond_its_scratch(race):
     rc = L.ersd_race_verify_noalloc(d.data_ptr(), d.data_ptr(), race.ERSD_F32, B, k, V, 1.0, 0, d.data_ptr(),
                                     d.data_ptr(), d.data_ptr(), None)
     assert rc == -7
+
+
+def test_noalloc_call_can_be_captured_in_a_graph_and_replayed(race):
+    """What the entry point is for: no allocation and no memset inside the call, so a captured call replays to the
+    same outputs, also after other work on the device and after another call has used the library's scratch array."""
+    race.noalloc_prepare()      # the address and occupancy queries happen here, before the capture
+    w = wl.shrink(wl.WORKLOADS[1], B=8, k=4, V=65536)
+    x = wl.make_inputs(w, "cuda")
+    ref = race.race_verify(x["draft"], x["target"], w.temperature, w.seed)
+    out = _outs(w.B, w.k)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(g, stream=s):
+            race.race_verify_noalloc(x["draft"], x["target"], w.temperature, w.seed, out)
+    torch.cuda.synchronize()
+    other = wl.make_inputs(wl.shrink(wl.WORKLOADS[2], B=3, k=2, V=30000), "cuda")
+    for rep in range(3):
+        for o in out:
+            o.fill_(-7)
+        race.race_verify_noalloc(other["draft"], other["target"], 0.7, 5, _outs(3, 2))   # overwrites the scratch array
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert all(torch.equal(a, b) for a, b in zip(out, ref)), f"replay {rep}"
+        y = torch.randn(1 << 20, device="cuda").sum().item()   # eager work between replays
+        assert y == y
