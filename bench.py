@@ -22,7 +22,7 @@ import time
 import torch
 
 PEAK_HBM_GBS = 8000.0
-ARITHMETIC = "u32 Philox + f32 bound filter on every token, f64 scores where f32 cannot decide"
+ARITHMETIC = "u32+f32 filter, f64 decide"  # u32 Philox + f32 bound filter on every token, f64 scores where f32 cannot decide
 
 # HBM bytes per race-kernel launch from rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE, each scaled by what the same
 # counter reads for a 1 GiB copy); NOT measured in this run: the figures of the summaries under profiles/, which
