@@ -224,8 +224,8 @@ int ersd_plan_describe_host(int variant, int32_t B, int32_t m, int32_t k_or_N, i
  * context's draft row is not read), as the library derives it on the device from (parent, rank).  Rows are the
  * B * (N + 1) contexts; a context with a draft row costs 10 per group, one without 5.
  */
-int ersd_arrival_plan_describe_host(int32_t B, int32_t N, int32_t V, const int32_t* need_host, uint32_t blocks,
-                                    uint32_t* out_G, uint32_t* out_nslot, uint64_t* block_start,
+int ersd_arrival_plan_describe_host(int32_t B, int32_t N, int32_t V, ersd_dtype dt, const int32_t* need_host,
+                                    uint32_t blocks, uint32_t* out_G, uint32_t* out_nslot, uint64_t* block_start,
                                     uint32_t* row_first, uint32_t* row_last);
 
 /*

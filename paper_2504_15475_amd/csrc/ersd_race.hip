@@ -1860,8 +1860,9 @@ ArrLayout arrival_layout(int32_t B, int32_t N, int32_t V) {
 // The partition of an arrival tree: every field is set here (the struct is value-initialised, `fast` stays 0: plain
 // division, because the totals are known only where the weight table is), and the table's totals are filled in by
 // part_on_device where the table can be read.
-Part make_arrival_part(int32_t B, int32_t C, int32_t V, uint32_t blocks, const uint32_t* wprefix) {
+Part make_arrival_part(int32_t B, int32_t C, int32_t V, uint32_t blocks, const uint32_t* wprefix, ersd_dtype dt) {
     Part p{};
+    p.amask = align_mask_for(dt);  // shares start on whole cache lines of the rows
     p.V8 = (uint32_t)(((int64_t)V + 7) / 8);
     p.kd = 0;                    // no closed-form pair rows: the table decides
     p.kt = (uint32_t)C;
@@ -1903,7 +1904,7 @@ int launch_arrival_tree(const void* dl, int64_t qstride, const void* tl, int64_t
         meta.wprefix = reinterpret_cast<uint32_t*>(base + l.wprefix);
     }
 
-    const Part p = make_arrival_part(B, C, V, (uint32_t)blocks, meta.wprefix);
+    const Part p = make_arrival_part(B, C, V, (uint32_t)blocks, meta.wprefix, dt);
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (!plan) hipLaunchKernelGGL(arrival_meta_kernel, dim3(1), dim3(kThreads), 0, s, parent, rank, N, meta);
@@ -2294,10 +2295,11 @@ int ersd_plan_describe_host(int variant, int32_t B, int32_t m, int32_t k_or_N, i
     return ERSD_OK;
 }
 
-int ersd_arrival_plan_describe_host(int32_t B, int32_t N, int32_t V, const int32_t* need_host, uint32_t blocks,
-                                    uint32_t* out_G, uint32_t* out_nslot, uint64_t* block_start, uint32_t* row_first,
-                                    uint32_t* row_last) {
+int ersd_arrival_plan_describe_host(int32_t B, int32_t N, int32_t V, ersd_dtype dt, const int32_t* need_host,
+                                    uint32_t blocks, uint32_t* out_G, uint32_t* out_nslot, uint64_t* block_start,
+                                    uint32_t* row_first, uint32_t* row_last) {
     if (!need_host || !out_G || !out_nslot) return ERSD_ERR_NULL_POINTER;
+    if (dt != ERSD_F32 && dt != ERSD_BF16) return ERSD_ERR_UNSUPPORTED_DTYPE;
     if (blocks < 1 || blocks > kMaxBlocks || !arrival_sizes_ok(B, N, V)) return ERSD_ERR_INVALID_ARG;
     const int32_t C = N + 1;
     // the weight table as the tree-shape kernel writes it: a context with a draft row costs as a pair row
@@ -2305,7 +2307,7 @@ int ersd_arrival_plan_describe_host(int32_t B, int32_t N, int32_t V, const int32
     if (!wprefix) return ERSD_ERR_INVALID_ARG;
     wprefix[0] = 0;
     for (int32_t c = 0; c < C; ++c) wprefix[c + 1] = wprefix[c] + (need_host[c] > 0 ? kWPair : kWSingle);
-    Part p = make_arrival_part(B, C, V, blocks, wprefix);
+    Part p = make_arrival_part(B, C, V, blocks, wprefix, dt);
     p.Us = (uint64_t)wprefix[C] * p.V8;   // what part_on_device reads from the table
     p.U = p.Us * (uint64_t)B;
     *out_G = p.G;

@@ -470,7 +470,7 @@ def plan_describe(variant, B, m, k_or_N, V, blocks, dtype_code=ERSD_BF16):
                 row_last=last)
 
 
-def arrival_plan_describe(B, N, V, need, blocks):
+def arrival_plan_describe(B, N, V, need, blocks, dtype_code=ERSD_BF16):
     """Host-only view of an arrival tree's work partition; need: int32 [N+1] host array (arrivals per context)."""
     import numpy as np
     need = np.ascontiguousarray(np.asarray(need, dtype=np.int32))
@@ -480,9 +480,10 @@ def arrival_plan_describe(B, N, V, need, blocks):
     first = np.zeros(rows, dtype=np.uint32)
     last = np.zeros(rows, dtype=np.uint32)
     L = lib()
-    L.ersd_arrival_plan_describe_host.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
-                                                  ctypes.c_uint32] + [ctypes.c_void_p] * 5
-    _check(L.ersd_arrival_plan_describe_host(B, N, V, need.ctypes.data, blocks, ctypes.byref(G), ctypes.byref(nslot),
+    L.ersd_arrival_plan_describe_host.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int,
+                                                  ctypes.c_void_p, ctypes.c_uint32] + [ctypes.c_void_p] * 5
+    _check(L.ersd_arrival_plan_describe_host(B, N, V, dtype_code, need.ctypes.data, blocks, ctypes.byref(G),
+                                             ctypes.byref(nslot),
                                              start.ctypes.data, first.ctypes.data, last.ctypes.data))
     return dict(G=G.value, nslot=nslot.value, block_start=start[: G.value + 1], row_first=first, row_last=last)
 

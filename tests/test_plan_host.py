@@ -98,7 +98,7 @@ def test_arrival_tree_partition_stays_inside_the_job(oracle_mod, B, N, V, blocks
     for trial in range(3):
         parent, rank = _random_tree(rng, N, branching=int(rng.integers(1, 5)))
         _, need = oracle_mod.arrival_tree_shape(parent, rank, 8)
-        d = race.arrival_plan_describe(B, N, V, need, blocks)
+        d = race.arrival_plan_describe(B, N, V, need, blocks, race.ERSD_BF16 if trial % 2 else race.ERSD_F32)
         G, nslot, start = d["G"], d["nslot"], d["block_start"].astype(np.int64)
         rows, V8 = B * (N + 1), (V + 7) // 8
         assert 1 <= G <= blocks and len(start) == G + 1
@@ -115,7 +115,7 @@ def test_arrival_tree_partition_stays_inside_the_job(oracle_mod, B, N, V, blocks
             r = np.minimum(g // V8, rows - 1)
             return np.where(g >= rows * V8, cum[-1], cum[r] + (g - r * V8) * w[r])
         costs = np.diff(units(start))
-        assert costs.max() - costs.min() <= 22
+        assert costs.max() - costs.min() <= 22 + 2 * 8 * 10      # share starts are aligned to 8 (bf16) or 4 groups
         # the workspace covers these slots
         for code in (race.ERSD_F32, race.ERSD_BF16):
             assert race.arrival_tree_workspace_bytes(B, N, V, code) >= rows * (2 * 80 + 272) * nslot
