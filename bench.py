@@ -27,7 +27,7 @@ ARITHMETIC = "u32+f32 filter, f64 decide"  # u32 Philox + f32 bound filter on ev
 # HBM bytes per race-kernel launch from rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE, each scaled by what the same
 # counter reads for a 1 GiB copy); NOT measured in this run: the figures of the summaries under profiles/, which
 # name the commands that produced them.
-PROFILED_TRAFFIC_BYTES = {1: 279970329, 2: 5141420040, 3: 1117815658, 4: 1049642127}
+PROFILED_TRAFFIC_BYTES = {1: 279967334, 2: 5141426511, 3: 1117813011, 4: 1049643334}
 PROFILE_FILE = {1: "profiles/race_kernel_seq_B64_k8_V128256_bf16.md", 2: "profiles/race_kernel_seq_B256_k16_V152064_f32.md",
                 3: "profiles/race_kernel_multi_B32_m8_k8_V128256_bf16.md", 4: "profiles/race_kernel_tree_B16_N64_V256000_bf16.md"}
 
