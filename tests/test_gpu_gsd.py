@@ -50,7 +50,7 @@ def check(race, oracle_mod, draft, target, T, seed, note=""):
         assert nxt[b] == o["next_token"][b], f"sequence {b}: next_token {nxt[b]} != {o['next_token'][b]}"
     print(f"[case] ok: skipped {skipped}, tokens with rivals {loose}, mean accepted {o['accept_len'].mean():.2f}",
           flush=True)
-    assert skipped + loose <= max(2, B // 20)
+    assert skipped + loose <= max(1, B // 50)      # (none is flagged in the committed cases)
     return o
 
 

@@ -69,7 +69,7 @@ def check(race, oracle_mod, draft, target, parent, rank, T, seed, note=""):
             continue
         assert emitted[b, a] == o["emitted"][b, a], f"prompt {b}: drawn token {emitted[b, a]} != {o['emitted'][b, a]}"
     print(f"[case] ok: skipped {skipped}, draws with rivals {loose}, mean accepted {o['accept_len'].mean():.2f}", flush=True)
-    assert skipped + loose <= max(2, B // 20)
+    assert skipped + loose <= max(1, B // 50)      # (none is flagged in the committed cases)
     return o
 
 
