@@ -135,3 +135,27 @@ def test_full_size_tree_matches_oracle_on_a_sample(race, oracle_mod):
         assert int(acc[b]) == o["accept_len"][b] and int(node[b]) == o["accept_node"][b]
         if o["info"]["rivals"][b] == 0:
             assert emitted[b].cpu().numpy().tolist() == o["emitted"][b].tolist()
+
+
+def test_emitted_token_follows_the_target_law_on_the_gpu(race):
+    """No oracle: three alternatives at the root drafted by the library's own arrival race, verified by the library's
+    recursive rejection: the first emitted token must be distributed as softmax(target / T) (chi-square), and more
+    than one alternative must be accepted more often than 1 - D_TV."""
+    from scipy import stats
+    B, V, N, T = 40000, 12, 3, 0.9
+    g = torch.Generator(device="cuda")
+    g.manual_seed(3)
+    lp = 1.3 * torch.randn(V, generator=g, device="cuda")
+    lq = lp + 0.9 * torch.randn(V, generator=g, device="cuda")
+    target = lp.repeat(B, N + 1, 1).contiguous()
+    draft = lq.repeat(B, N + 1, 1).contiguous()
+    parent = torch.full((N,), -1, dtype=torch.int32, device="cuda")
+    rank = torch.arange(N, dtype=torch.int32, device="cuda")
+    tok = race.race_verify_arrival_tree(draft, target, parent, rank, T, 21)[0]
+    acc, node, emitted = race.gsd_verify_tree(draft, target, parent, rank, tok, T, 21)
+    first = emitted[:, 0].cpu().numpy()
+    p = torch.softmax(lp.double() / float(np.float32(T)), 0).cpu().numpy()
+    q = torch.softmax(lq.double() / float(np.float32(T)), 0).cpu().numpy()
+    chi2, pval = stats.chisquare(np.bincount(first, minlength=V), p * B)
+    assert pval > 1e-3, (chi2, pval)
+    assert (acc >= 1).float().mean().item() > 1.0 - 0.5 * np.abs(p - q).sum() + 0.02
